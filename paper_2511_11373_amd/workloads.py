@@ -1,0 +1,179 @@
+"""Seeded synthetic inputs for the routed-expert MoE FFN layer.
+
+The layer shape is that of the policy model the paper trains (Section 4.1,
+"Training Details": Qwen3-30B-A3B-Thinking-2507): hidden 2048, 128 routed
+experts, 8 experts per token, expert intermediate size 768, SwiGLU experts.
+Token counts stand in for the paper's workloads: a rollout decode step over a
+batch of concurrent responses (Section 4.1: 128 prompts x 8 responses) and a
+log-prob recompute chunk of one 16k-token segment (Section 2.3, segment
+rollout; Eq. 3 needs the recomputed token probabilities).
+
+This module only draws numbers.  It holds none of the layer's arithmetic and is
+the one module both the CPU oracle's tests and the GPU path's tests draw their
+inputs from; each tensor has its own independent random stream.
+
+bf16 tensors are returned as numpy uint16 bit patterns (numpy has no bf16).
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, Optional
+
+import numpy as np
+
+BF16 = "bf16"
+F32 = "f32"
+
+
+@dataclasses.dataclass(frozen=True)
+class MoEConfig:
+    name: str
+    T: int            # tokens
+    H: int            # hidden size
+    E: int            # routed experts
+    K: int            # experts per token
+    I: int            # expert intermediate size
+    dtype: str        # BF16 or F32: storage type of x and of every weight
+    renormalize: bool = True
+    zipf_s: Optional[float] = None   # router-bias skew exponent, None = no bias
+    seed: int = 0
+    sigma_w: float = 0.02            # standard deviation of every weight
+
+
+CONFIGS: Dict[str, MoEConfig] = {
+    "tiny":        MoEConfig("tiny", 64, 256, 8, 2, 128, F32),
+    "decode64":    MoEConfig("decode64", 64, 2048, 128, 8, 768, BF16),
+    "decode512":   MoEConfig("decode512", 512, 2048, 128, 8, 768, BF16),
+    "prefill16k":  MoEConfig("prefill16k", 16384, 2048, 128, 8, 768, BF16),
+    "skew4k":      MoEConfig("skew4k", 4096, 2048, 128, 8, 768, BF16, zipf_s=1.2),
+}
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); returns uint16 bits."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns to the fp32 values they denote (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+_CHUNK_ROWS = 1 << 22      # elements per independently seeded chunk (fixed: part of the recipe)
+
+
+def _fill_chunk(args):
+    seed, stream, j, view, sigma = args
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, stream, j])))
+    rng.standard_normal(size=view.shape, dtype=np.float32, out=view)
+    if sigma != 1.0:
+        view *= np.float32(sigma)
+
+
+def _normal(seed: int, stream: int, shape, sigma: float) -> np.ndarray:
+    """N(0, sigma^2) float32 tensor; chunk j of the flattened tensor comes from
+    the PCG64 stream seeded with (seed, stream, j), so the values do not depend
+    on how many threads fill it."""
+    n = int(np.prod(shape))
+    flat = np.empty(n, dtype=np.float32)
+    jobs = [(seed, stream, j, flat[o:o + _CHUNK_ROWS], sigma)
+            for j, o in enumerate(range(0, n, _CHUNK_ROWS))]
+    if len(jobs) == 1:
+        _fill_chunk(jobs[0])
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(_fill_chunk, jobs))
+    return flat.reshape(shape)
+
+
+def zipf_target_load(T: int, K: int, E: int, s: float) -> np.ndarray:
+    """Per-rank target row counts L_r = min(T, c * r^-s) with sum T*K.
+
+    One expert can serve at most T of the T*K assignments (a token picks K
+    distinct experts), so the head of the law is capped at T.
+    """
+    ranks = np.arange(1, E + 1, dtype=np.float64)
+    lo, hi = 0.0, float(T) * K * E
+    for _ in range(200):
+        c = 0.5 * (lo + hi)
+        tot = np.minimum(float(T), c * ranks ** (-s)).sum()
+        if tot < T * K:
+            lo = c
+        else:
+            hi = c
+    return np.minimum(float(T), 0.5 * (lo + hi) * ranks ** (-s))
+
+
+def zipf_router_bias(cfg: MoEConfig) -> np.ndarray:
+    """Per-expert additive router bias whose realised load is roughly Zipf(s).
+
+    Experts are ranked by a seeded permutation.  The bias starts from a
+    Gumbel-matching guess and is then calibrated for a fixed number of steps
+    against seeded i.i.d. Gaussian stand-in scores with the standard deviation
+    the real logits have (sigma_w * sqrt(H) for x ~ N(0,1)); the inputs
+    themselves are never looked at.  The realised load of a run is whatever the
+    layer's own router then produces; benchmarks report that histogram.
+    """
+    assert cfg.zipf_s is not None
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([cfg.seed, 6])))
+    perm = rng.permutation(cfg.E)                  # perm[r] = expert holding rank r+1
+    target = zipf_target_load(cfg.T, cfg.K, cfg.E, cfg.zipf_s)
+    sig = cfg.sigma_w * math.sqrt(cfg.H)
+    beta = sig * math.sqrt(6.0) / math.pi
+    n_mc = 4096
+    z = rng.standard_normal(size=(n_mc, cfg.E)) * sig
+    b_rank = -cfg.zipf_s * beta * np.log(np.arange(1, cfg.E + 1, dtype=np.float64))
+    tgt = target * (n_mc / cfg.T)
+    for _ in range(30):
+        s = z + b_rank[None, :]
+        top = np.argpartition(-s, cfg.K - 1, axis=1)[:, :cfg.K]
+        real = np.bincount(top.ravel(), minlength=cfg.E).astype(np.float64)
+        b_rank = b_rank + 0.5 * beta * (np.log(tgt) - np.log(np.maximum(real, 1.0)))
+    bias = np.empty(cfg.E, dtype=np.float32)
+    bias[perm] = b_rank.astype(np.float32)
+    return bias
+
+
+def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True) -> Dict[str, np.ndarray]:
+    """Draw x, the router weight, the three expert weights and the router bias.
+
+    Returns a dict with, for every tensor name in (x, w_router, w_gate, w_up,
+    w_down): `<name>` in storage form (float32 array, or uint16 bf16 bits) and
+    `<name>_f32`, the same values as float32 (what a CPU reference consumes;
+    left out when `want_f32` is false).
+    `router_bias` is float32 [E] or None.  `weight_set` > 0 draws a different,
+    equally distributed set of expert weights (for cache-defeating rotation in
+    benchmarks); x and the router are unchanged.
+    """
+    T, H, E, I = cfg.T, cfg.H, cfg.E, cfg.I
+    base = 16 * weight_set
+    raw = {
+        "x": _normal(cfg.seed, 1, (T, H), 1.0),
+        "w_router": _normal(cfg.seed, 2, (E, H), cfg.sigma_w),
+        "w_gate": _normal(cfg.seed, 3 + base, (E, I, H), cfg.sigma_w),
+        "w_up": _normal(cfg.seed, 4 + base, (E, I, H), cfg.sigma_w),
+        "w_down": _normal(cfg.seed, 5 + base, (E, H, I), cfg.sigma_w),
+    }
+    out: Dict[str, np.ndarray] = {}
+    for k, v in raw.items():
+        if cfg.dtype == BF16:
+            bits = f32_to_bf16_bits(v)
+            out[k] = bits
+            if want_f32:
+                out[k + "_f32"] = bf16_bits_to_f32(bits)
+        else:
+            out[k] = v
+            if want_f32:
+                out[k + "_f32"] = v
+    out["router_bias"] = zipf_router_bias(cfg) if cfg.zipf_s is not None else None
+    return out
+
+
+def small_config(T: int, H: int, E: int, K: int, I: int, dtype: str = F32, seed: int = 0,
+                 renormalize: bool = True, sigma_w: float = 0.02) -> MoEConfig:
+    return MoEConfig(f"T{T}H{H}E{E}K{K}I{I}", T, H, E, K, I, dtype, renormalize, None, seed, sigma_w)
