@@ -1,0 +1,176 @@
+// C ABI of the MoE FFN library: argument validation (host only, before any HIP
+// call), workspace carving, and the launch sequences.
+#include "moe_internal.hpp"
+
+namespace moe {
+
+static moe_status_t check_shape(const moe_shape_t *s) {
+    if (!s) return MOE_ERR_NULL;
+    if (s->dtype != MOE_BF16 && s->dtype != MOE_F32) return MOE_ERR_DTYPE;
+    if (s->T < 0 || s->H < 1 || s->E < 1 || s->K < 1 || s->I < 1) return MOE_ERR_SHAPE;
+    if (s->K > s->E || s->E > kMaxExperts) return MOE_ERR_SHAPE;
+    if (s->H % 8 != 0 || s->I % 8 != 0) return MOE_ERR_SHAPE;
+    const long long lim = 0x7FFFFFFFll;
+    if ((long long)s->T * s->K > lim || (long long)s->T * s->E > lim) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+static bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static size_t elt_size(const moe_shape_t &s) { return s.dtype == MOE_BF16 ? 2 : 4; }
+
+template <typename P>
+static void take(char *&cur, P *&field, size_t bytes) {
+    field = reinterpret_cast<P *>(cur);
+    cur += align256(bytes);
+}
+
+Workspace carve_workspace(const moe_shape_t &s, void *base) {
+    Workspace w;
+    char *cur = reinterpret_cast<char *>(base);
+    const size_t n = (size_t)s.T * s.K;
+    const size_t nchunks = (n + kPermChunk - 1) / kPermChunk;
+    const size_t max_tiles = n / kMinTokenTile + (size_t)s.E;
+    take(cur, w.logit_part, sizeof(double) * (size_t)router_ksplit(s) * s.T * s.E);
+    take(cur, w.topk_idx, sizeof(int32_t) * n);
+    take(cur, w.topk_w, sizeof(float) * n);
+    take(cur, w.expert_offsets, sizeof(int32_t) * ((size_t)s.E + 1));
+    take(cur, w.row_to_assign, sizeof(int32_t) * n);
+    take(cur, w.assign_to_row, sizeof(int32_t) * n);
+    take(cur, w.chunk_base, sizeof(int32_t) * nchunks * s.E);
+    take(cur, w.tile_map, sizeof(int32_t) * (2 * max_tiles + 4));
+    take(cur, w.act, sizeof(bf16_t) * n * s.I);
+    void *y = nullptr;
+    take(cur, y, elt_size(s) * n * s.H);
+    w.y_perm = y;
+    w.total = (size_t)(cur - reinterpret_cast<char *>(base));
+    return w;
+}
+
+static moe_status_t check_ws(const moe_shape_t &s, const void *ws, size_t ws_bytes) {
+    if (!ws) return MOE_ERR_WORKSPACE;
+    if (misaligned(ws)) return MOE_ERR_ALIGN;
+    if (ws_bytes < carve_workspace(s, nullptr).total) return MOE_ERR_WORKSPACE;
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char *moe_status_string(moe_status_t status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "a required pointer is NULL";
+        case MOE_ERR_SHAPE: return "unsupported shape";
+        case MOE_ERR_DTYPE: return "unknown dtype";
+        case MOE_ERR_WORKSPACE: return "workspace missing or too small";
+        case MOE_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case MOE_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+moe_status_t moe_workspace_bytes(const moe_shape_t *shape, size_t *out_bytes) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!out_bytes) return MOE_ERR_NULL;
+    *out_bytes = carve_workspace(*shape, nullptr).total;
+    return MOE_OK;
+}
+
+moe_status_t moe_route_topk(const moe_shape_t *shape, const void *x, const void *w_router,
+                            const float *router_bias, int32_t *topk_idx, float *topk_w,
+                            void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(topk_idx) || misaligned(topk_w))
+        return MOE_ERR_ALIGN;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    Workspace w = carve_workspace(*shape, ws);
+    return launch_route(*shape, x, w_router, router_bias, w.logit_part, topk_idx, topk_w, (hipStream_t)stream) == hipSuccess
+               ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status_t moe_permute(const moe_shape_t *shape, const int32_t *topk_idx, const void *x,
+                         int32_t *expert_offsets, int32_t *row_to_assign, int32_t *assign_to_row,
+                         void *x_perm, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !expert_offsets || !row_to_assign || !assign_to_row) return MOE_ERR_NULL;
+    if (x_perm && !x) return MOE_ERR_NULL;
+    if (misaligned(topk_idx) || misaligned(x) || misaligned(expert_offsets) || misaligned(row_to_assign) ||
+        misaligned(assign_to_row) || misaligned(x_perm))
+        return MOE_ERR_ALIGN;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;   // nothing enqueued; expert_offsets is left untouched
+    Workspace w = carve_workspace(*shape, ws);
+    hipStream_t hs = (hipStream_t)stream;
+    if (launch_permute(*shape, topk_idx, expert_offsets, row_to_assign, assign_to_row, w.chunk_base, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (x_perm && launch_gather_rows(*shape, x, row_to_assign, x_perm, hs) != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+moe_status_t moe_grouped_swiglu(const moe_shape_t *shape, const void *x_perm, const int32_t *expert_offsets,
+                                const void *w_gate, const void *w_up, const void *w_down, void *y_perm,
+                                void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!x_perm || !expert_offsets || !w_gate || !w_up || !w_down || !y_perm) return MOE_ERR_NULL;
+    if (misaligned(x_perm) || misaligned(expert_offsets) || misaligned(w_gate) || misaligned(w_up) ||
+        misaligned(w_down) || misaligned(y_perm))
+        return MOE_ERR_ALIGN;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    Workspace w = carve_workspace(*shape, ws);
+    return launch_grouped_swiglu(*shape, x_perm, nullptr, expert_offsets, w_gate, w_up, w_down, w.act, w.tile_map,
+                                 y_perm, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status_t moe_combine(const moe_shape_t *shape, const void *y_perm, const int32_t *assign_to_row,
+                         const float *topk_w, void *out, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!y_perm || !assign_to_row || !topk_w || !out) return MOE_ERR_NULL;
+    if (misaligned(y_perm) || misaligned(assign_to_row) || misaligned(topk_w) || misaligned(out)) return MOE_ERR_ALIGN;
+    if (shape->T == 0) return MOE_OK;
+    return launch_combine(*shape, y_perm, assign_to_row, topk_w, out, (hipStream_t)stream) == hipSuccess
+               ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_router,
+                         const float *router_bias, const void *w_gate, const void *w_up,
+                         const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                         void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !out) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
+        misaligned(w_down) || misaligned(out) || misaligned(topk_idx_out) || misaligned(topk_w_out))
+        return MOE_ERR_ALIGN;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    const moe_shape_t &s = *shape;
+    Workspace w = carve_workspace(s, ws);
+    hipStream_t hs = (hipStream_t)stream;
+    int32_t *idx = topk_idx_out ? topk_idx_out : w.topk_idx;
+    float *tw = topk_w_out ? topk_w_out : w.topk_w;
+    if (launch_route(s, x, w_router, router_bias, w.logit_part, idx, tw, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_permute(s, idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (launch_grouped_swiglu(s, x, w.row_to_assign, w.expert_offsets, w_gate, w_up, w_down, w.act, w.tile_map,
+                              w.y_perm, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (launch_combine(s, w.y_perm, w.assign_to_row, tw, out, hs) != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+}  // extern "C"

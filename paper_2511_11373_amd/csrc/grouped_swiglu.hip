@@ -1,0 +1,219 @@
+// Grouped SwiGLU expert FFN on the bf16 matrix cores.
+//
+// Two GEMM passes over the expert-sorted rows, both with the weight rows as the
+// MFMA "A" operand and the token rows as the "B" operand, so that a lane ends
+// up holding four consecutive output features of one token:
+//   pass 1: act[r, i]  = bf16( silu(Wg[e,i,:] . x_r) * (Wu[e,i,:] . x_r) )
+//   pass 2: y[r, j]    = Wd[e,j,:] . act[r,:]
+// Row tiles never straddle two experts: a small kernel turns expert_offsets into
+// a list of (expert, first row) tiles on the device, and the GEMM grids are
+// sized from an upper bound so the host never reads the offsets.
+#include "moe_internal.hpp"
+
+namespace moe {
+
+// ---- tile list -----------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void build_tile_map_kernel(const int32_t *__restrict__ off, int E, int BT,
+                                                              int max_tiles, int32_t *__restrict__ tile_map) {
+    __shared__ int first[kMaxExperts + 1];
+    for (int e = threadIdx.x; e < E; e += 1024) first[e] = (off[e + 1] - off[e] + BT - 1) / BT;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { const int v = first[e]; first[e] = run; run += v; }
+        first[E] = run;
+        tile_map[2 * max_tiles] = run < max_tiles ? run : max_tiles;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 1024) {
+        const int r0 = off[e];
+        for (int t = first[e], i = 0; t < first[e + 1] && t < max_tiles; ++t, ++i) {
+            tile_map[2 * t] = e;
+            tile_map[2 * t + 1] = r0 + i * BT;
+        }
+    }
+}
+
+// ---- global -> register staging of 8 consecutive elements as packed bf16 -------------------
+__device__ __forceinline__ u32x4 load8_bf16(const bf16_t *p, bool ok) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (ok) v = *reinterpret_cast<const u32x4 *>(p);
+    return v;
+}
+__device__ __forceinline__ u32x4 load8_bf16(const float *p, bool ok) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (ok) {
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+        const f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+        v[0] = pack_bf16x2(a[0], a[1]); v[1] = pack_bf16x2(a[2], a[3]);
+        v[2] = pack_bf16x2(b[0], b[1]); v[3] = pack_bf16x2(b[2], b[3]);
+    }
+    return v;
+}
+__device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d) {
+    u32x2 v = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
+    *reinterpret_cast<u32x2 *>(p) = v;
+}
+__device__ __forceinline__ void store4(float *p, float a, float b, float c, float d) {
+    f32x4 v = {a, b, c, d};
+    *reinterpret_cast<f32x4 *>(p) = v;
+}
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+// ---- tiled grouped GEMM --------------------------------------------------------------------
+// Block = WW x WT waves; each wave owns MW x MT tiles of 32 weight rows x 32 tokens
+// (v_mfma_f32_32x32x16_bf16: lane l feeds row l%32, k = 8*(l/32)..+7 of both operands; result
+// register r is D[8*(r/4) + 4*(l/32) + r%4][l%32]).
+//   GATE_UP: weight tile = BW rows of Wg and the same BW rows of Wu, output act (bf16).
+//   else   : weight tile = BW rows of Wd, output y in the storage type SO.
+// SX/SW: storage type of the token rows / of the weights (bf16 bits or float, rounded on load).
+template <typename SX, typename SW, typename SO, bool GATE_UP, int WW, int WT, int MW, int MT>
+__global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
+    const SX *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
+    const int32_t *__restrict__ off, const int32_t *__restrict__ tile_map, int max_tiles,
+    const SW *__restrict__ w0, const SW *__restrict__ w1, SO *__restrict__ outp,
+    int KD /* reduction length */, int NW /* weight rows per expert */) {
+    constexpr int NT = WW * WT * 64;
+    constexpr int BW = WW * MW * 32, BT = WT * MT * 32, BK = 64, LDK = BK + 8;
+    constexpr int NMAT = GATE_UP ? 2 : 1;
+    constexpr int WCH = NMAT * BW * (BK / 8), XCH = BT * (BK / 8);      // 16-byte chunks per k tile
+    constexpr int WPT = (WCH + NT - 1) / NT, XPT = (XCH + NT - 1) / NT;
+    __shared__ __attribute__((aligned(16))) bf16_t Ws[NMAT * BW * LDK];
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[BT * LDK];
+
+    const int tile = blockIdx.x;
+    if (tile >= tile_map[2 * max_tiles]) return;
+    const int e = tile_map[2 * tile], row0 = tile_map[2 * tile + 1];
+    const int row_end = off[e + 1];
+    const int wrow0 = blockIdx.y * BW;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ww = wave % WW, wt = wave / WW;
+
+    // staging assignments: chunk c -> (row c/8, k piece c%8)
+    const SW *wsrc[WPT]; bool wok[WPT]; int wdst[WPT];
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        const int c = tid + i * NT;
+        const int mat = c / (BW * 8), r = (c / 8) % BW, kc = c % 8;
+        const int wr = wrow0 + r;
+        wok[i] = c < WCH && wr < NW;
+        const SW *base = (GATE_UP && mat == 1) ? w1 : w0;
+        wsrc[i] = base + ((size_t)e * NW + (wok[i] ? wr : 0)) * KD + kc * 8;
+        wdst[i] = (mat * BW + r) * LDK + kc * 8;
+    }
+    const SX *xsrc[XPT]; bool xok[XPT]; int xdst[XPT];
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+        const int c = tid + i * NT;
+        const int r = c / 8, kc = c % 8;
+        const int row = row0 + r;
+        xok[i] = c < XCH && row < row_end;
+        int src = xok[i] ? row : row0;
+        if (row_map) src = row_map[src] / K_assign;
+        xsrc[i] = xrows + (size_t)src * KD + kc * 8;
+        xdst[i] = r * LDK + kc * 8;
+    }
+
+    f32x16 acc[NMAT][MW][MT];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+        for (int a = 0; a < MW; ++a)
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[m][a][b][r] = 0.f;
+
+    u32x4 wreg[WPT], xreg[XPT];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) wreg[i] = load8_bf16(wsrc[i] + k0, wok[i] && (k0 + (tid + i * NT) % 8 * 8) < KD);
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) xreg[i] = load8_bf16(xsrc[i] + k0, xok[i] && (k0 + (tid + i * NT) % 8 * 8) < KD);
+    };
+    fetch(0);
+    const int arow = lane & 31, akq = (lane >> 5) * 8;
+    for (int k0 = 0; k0 < KD; k0 += BK) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < WPT; ++i)
+            if (tid + i * NT < WCH) *reinterpret_cast<u32x4 *>(&Ws[wdst[i]]) = wreg[i];
+#pragma unroll
+        for (int i = 0; i < XPT; ++i)
+            if (tid + i * NT < XCH) *reinterpret_cast<u32x4 *>(&Xs[xdst[i]]) = xreg[i];
+        __syncthreads();
+        if (k0 + BK < KD) fetch(k0 + BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 bop[MT];
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+                bop[b] = *reinterpret_cast<const bf16x8 *>(&Xs[((wt * MT + b) * 32 + arow) * LDK + ks * 16 + akq]);
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+                for (int a = 0; a < MW; ++a) {
+                    const bf16x8 aop = *reinterpret_cast<const bf16x8 *>(
+                        &Ws[(m * BW + (ww * MW + a) * 32 + arow) * LDK + ks * 16 + akq]);
+#pragma unroll
+                    for (int b = 0; b < MT; ++b)
+                        acc[m][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[b], acc[m][a][b], 0, 0, 0);
+                }
+        }
+    }
+
+    // epilogue: lane holds token (l%32), features 8*(r/4) + 4*(l/32) + 0..3
+#pragma unroll
+    for (int a = 0; a < MW; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+            const int row = row0 + (wt * MT + b) * 32 + (lane & 31);
+            if (row >= row_end) continue;
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int f = wrow0 + (ww * MW + a) * 32 + 8 * rq + 4 * (lane >> 5);
+                if (f >= NW) continue;
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (GATE_UP) v[j] = silu_mul(acc[0][a][b][4 * rq + j], acc[NMAT - 1][a][b][4 * rq + j]);
+                    else v[j] = acc[0][a][b][4 * rq + j];
+                }
+                store4(outp + (size_t)row * NW + f, v[0], v[1], v[2], v[3]);
+            }
+        }
+}
+
+template <typename S>
+static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int32_t *row_map,
+                               const int32_t *off, const S *wg, const S *wu, const S *wd, bf16_t *act,
+                               int32_t *tile_map, S *y_perm, hipStream_t st) {
+    constexpr int WW = 2, WT = 2, MW = 1, MT = 1;
+    constexpr int BW = WW * MW * 32, BT = WT * MT * 32;
+    const int n = s.T * s.K;
+    const int max_tiles = n / BT + (s.E < n ? s.E : n);
+    hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, s.E, BT, max_tiles, tile_map);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT>), dim3(max_tiles, (s.I + BW - 1) / BW),
+                       dim3(WW * WT * 64), 0, st, x_rows, row_map, s.K, off, tile_map, max_tiles, wg, wu, act, s.H, s.I);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MW, MT>), dim3(max_tiles, (s.H + BW - 1) / BW),
+                       dim3(WW * WT * 64), 0, st, (const bf16_t *)act, (const int32_t *)nullptr, 1, off, tile_map,
+                       max_tiles, wd, wd, y_perm, s.I, s.H);
+    return hipGetLastError();
+}
+
+hipError_t launch_grouped_swiglu(const moe_shape_t &s, const void *x_rows, const int32_t *row_map,
+                                 const int32_t *expert_offsets, const void *w_gate, const void *w_up,
+                                 const void *w_down, bf16_t *act, int32_t *tile_map, void *y_perm,
+                                 hipStream_t st) {
+    if (s.dtype == MOE_BF16)
+        return launch_typed<bf16_t>(s, (const bf16_t *)x_rows, row_map, expert_offsets, (const bf16_t *)w_gate,
+                                    (const bf16_t *)w_up, (const bf16_t *)w_down, act, tile_map, (bf16_t *)y_perm, st);
+    return launch_typed<float>(s, (const float *)x_rows, row_map, expert_offsets, (const float *)w_gate,
+                               (const float *)w_up, (const float *)w_down, act, tile_map, (float *)y_perm, st);
+}
+
+}  // namespace moe

@@ -1,0 +1,77 @@
+// Internal declarations shared by the HIP translation units of the MoE FFN
+// library (gfx950 only).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe_ffn.h"
+
+namespace moe {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits in memory
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;   // one MFMA bf16 operand
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 1024;      // limit of the top-k and permutation kernels
+constexpr int kPermChunk = 512;        // assignments handled by one wave of the permutation kernels
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned int b) { return __uint_as_float(b << 16); }
+
+// float -> bf16 bits, round to nearest even (inputs are finite).
+__device__ __forceinline__ unsigned int float_to_bf16_bits(float f) {
+    unsigned int u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Workspace carving.  Every region starts 256-byte aligned.
+struct Workspace {
+    double  *logit_part;     // [ksplit, T, E] partial logit sums
+    int32_t *topk_idx;       // [T*K]
+    float   *topk_w;         // [T*K]
+    int32_t *expert_offsets; // [E+1]
+    int32_t *row_to_assign;  // [T*K]
+    int32_t *assign_to_row;  // [T*K]
+    int32_t *chunk_base;     // [nchunks, E] per-chunk histogram, then per-chunk first row
+    int32_t *tile_map;       // [2*max_tiles + 4]: tile -> (expert, first row), then tile count
+    bf16_t  *act;            // [T*K, I] bf16 activations silu(g)*u
+    void    *y_perm;         // [T*K, H] dtype
+    size_t   total;
+};
+
+constexpr int kMaxLogitSplit = 16;
+constexpr int kMinTokenTile = 16;      // smallest row tile any GEMM variant uses (bounds the tile map)
+
+Workspace carve_workspace(const moe_shape_t &s, void *base);
+
+int router_ksplit(const moe_shape_t &s);
+
+// Launchers (all enqueue on `st`, return the first HIP launch error).
+hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_router, const float *bias,
+                        double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st);
+hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t *expert_offsets,
+                          int32_t *row_to_assign, int32_t *assign_to_row, int32_t *chunk_base,
+                          hipStream_t st);
+hipError_t launch_gather_rows(const moe_shape_t &s, const void *x, const int32_t *row_to_assign,
+                              void *x_perm, hipStream_t st);
+// x_rows: either x_perm (row_map == nullptr) or x with row_map = row_to_assign (row r reads x[row_map[r]/K]).
+hipError_t launch_grouped_swiglu(const moe_shape_t &s, const void *x_rows, const int32_t *row_map,
+                                 const int32_t *expert_offsets, const void *w_gate, const void *w_up,
+                                 const void *w_down, bf16_t *act, int32_t *tile_map, void *y_perm,
+                                 hipStream_t st);
+hipError_t launch_combine(const moe_shape_t &s, const void *y_perm, const int32_t *assign_to_row,
+                          const float *topk_w, void *out, hipStream_t st);
+
+}  // namespace moe

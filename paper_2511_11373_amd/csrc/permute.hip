@@ -1,0 +1,154 @@
+// Expert-sorted permutation: a stable counting sort of the T*K assignments by
+// expert id, in three steps (per-chunk LDS histograms, a scan over chunks and
+// experts, a stable scatter).  Ranks come from ballots and prefix sums, never
+// from the return value of an atomic, so the order inside an expert's segment
+// is the assignment order and the result is unique.
+#include "moe_internal.hpp"
+
+namespace moe {
+
+// Step 1: one wave per chunk of kPermChunk assignments; per-chunk histogram [nchunks, E].
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__restrict__ idx, int n, int E,
+                                                           int32_t *__restrict__ chunk_base) {
+    extern __shared__ int hist_all[];   // [4][E]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + wave;
+    int *hist = hist_all + (size_t)wave * E;
+    for (int e = lane; e < E; e += 64) hist[e] = 0;
+    __syncthreads();
+    const int a0 = chunk * kPermChunk;
+    if (a0 < n) {
+        const int a1 = min(a0 + kPermChunk, n);
+        for (int a = a0 + lane; a < a1; a += 64) atomicAdd(&hist[idx[a]], 1);   // counts: order free
+    }
+    __syncthreads();
+    if (a0 < n)
+        for (int e = lane; e < E; e += 64) chunk_base[(size_t)chunk * E + e] = hist[e];
+}
+
+// Step 2: one block.  Turns the histograms into the first output row of every (chunk, expert) and
+// writes expert_offsets.  Thread (p, e): p-th slice of the chunks, expert e (+ a loop when E > blockDim/P).
+__global__ __launch_bounds__(1024) void permute_scan_kernel(int32_t *__restrict__ chunk_base, int nchunks, int E,
+                                                            int32_t *__restrict__ expert_offsets) {
+    __shared__ int part[1024];       // [P][Epad] slice sums, Epad*P <= 1024
+    __shared__ int etotal[kMaxExperts + 1];
+    // P slices of the chunk range per expert, experts processed in groups of G = 1024 / P.
+    int P = 1;
+    while (P < 16 && P * 2 * E <= 1024 && P * 2 <= nchunks) P *= 2;
+    const int G = 1024 / P;
+    const int cps = (nchunks + P - 1) / P;
+    for (int eg = 0; eg < E; eg += G) {
+        const int p = threadIdx.x / G, e = eg + threadIdx.x % G;
+        const int cb = p * cps, ce = min(cb + cps, nchunks);
+        int s = 0;
+        if (p < P && e < E)
+            for (int c = cb; c < ce; ++c) s += chunk_base[(size_t)c * E + e];
+        part[threadIdx.x] = s;
+        __syncthreads();
+        if (p < P && e < E) {
+            int before = 0, tot = 0;
+            for (int pp = 0; pp < P; ++pp) {
+                const int v = part[pp * G + threadIdx.x % G];
+                if (pp < p) before += v;
+                tot += v;
+            }
+            if (p == 0) etotal[e] = tot;
+            int run = before;       // rows of expert e in chunks before slice p
+            for (int c = cb; c < ce; ++c) {
+                const int v = chunk_base[(size_t)c * E + e];
+                chunk_base[(size_t)c * E + e] = run;
+                run += v;
+            }
+        }
+        __syncthreads();
+    }
+    // exclusive scan over experts (serial; E <= 1024)
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { const int v = etotal[e]; etotal[e] = run; run += v; }
+        etotal[E] = run;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e <= E; e += 1024) expert_offsets[e] = etotal[e];
+    for (size_t i = threadIdx.x; i < (size_t)nchunks * E; i += 1024) chunk_base[i] += etotal[i % E];
+}
+
+// Step 3: one wave per chunk.  Walks its assignments 64 at a time in order; lanes holding the same
+// expert find each other with log2(E) ballots; row = running first row of that expert + number of
+// lower lanes in the group.
+__global__ __launch_bounds__(256) void permute_scatter_kernel(const int32_t *__restrict__ idx, int n, int E,
+                                                              int ebits, const int32_t *__restrict__ chunk_base,
+                                                              int32_t *__restrict__ row_to_assign,
+                                                              int32_t *__restrict__ assign_to_row) {
+    extern __shared__ int next_all[];   // [4][E] next free row per expert, private to a wave
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + wave;
+    const int a0 = chunk * kPermChunk;
+    if (a0 >= n) return;
+    volatile int *next_row = next_all + (size_t)wave * E;
+    for (int e = lane; e < E; e += 64) next_row[e] = chunk_base[(size_t)chunk * E + e];
+    __builtin_amdgcn_wave_barrier();
+    const int a1 = min(a0 + kPermChunk, n);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int ab = a0; ab < a1; ab += 64) {
+        const int a = ab + lane;
+        const bool live = a < a1;
+        const int e = live ? idx[a] : 0;
+        unsigned long long peers = __ballot(live);
+        for (int b = 0; b < ebits; ++b) {
+            const unsigned long long has = __ballot((e >> b) & 1);
+            peers &= ((e >> b) & 1) ? has : ~has;
+        }
+        if (live) {
+            const int rank = __popcll(peers & below);
+            const int row = next_row[e] + rank;
+            row_to_assign[row] = a;
+            assign_to_row[a] = row;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (live && (peers & below) == 0ull) next_row[e] = next_row[e] + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// x_perm[r,:] = x[row_to_assign[r] / K,:]; 16-byte pieces, one block per 4 rows.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const u32x4 *__restrict__ x, const int32_t *__restrict__ row_to_assign,
+                                                          u32x4 *__restrict__ x_perm, int n, int K, int vec_per_row) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n) return;
+    const int t = row_to_assign[r] / K;
+    for (int v = threadIdx.x & 63; v < vec_per_row; v += 64)
+        x_perm[(size_t)r * vec_per_row + v] = x[(size_t)t * vec_per_row + v];
+}
+
+hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t *expert_offsets,
+                          int32_t *row_to_assign, int32_t *assign_to_row, int32_t *chunk_base,
+                          hipStream_t st) {
+    const int n = s.T * s.K;
+    const int nchunks = (n + kPermChunk - 1) / kPermChunk;
+    const size_t smem = (size_t)4 * s.E * sizeof(int);
+    dim3 grid((nchunks + 3) / 4);
+    hipLaunchKernelGGL(permute_hist_kernel, grid, dim3(256), smem, st, topk_idx, n, s.E, chunk_base);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, chunk_base, nchunks, s.E, expert_offsets);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    int ebits = 0;
+    while ((1 << ebits) < s.E) ++ebits;
+    hipLaunchKernelGGL(permute_scatter_kernel, grid, dim3(256), smem, st, topk_idx, n, s.E, ebits, chunk_base,
+                       row_to_assign, assign_to_row);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const moe_shape_t &s, const void *x, const int32_t *row_to_assign,
+                              void *x_perm, hipStream_t st) {
+    const int n = s.T * s.K;
+    const int elt = s.dtype == MOE_BF16 ? 2 : 4;
+    const int vec_per_row = s.H * elt / 16;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((n + 3) / 4), dim3(256), 0, st, (const u32x4 *)x, row_to_assign,
+                       (u32x4 *)x_perm, n, s.K, vec_per_row);
+    return hipGetLastError();
+}
+
+}  // namespace moe

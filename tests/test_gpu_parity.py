@@ -1,0 +1,178 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by
+element on the same seeded inputs.  Integer results (expert ids, offsets, both
+permutation maps, gathered rows) must be identical; floating-point results must
+stay within max-abs 2e-2 and relative L2 1e-2 of the (unrounded, double) oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_11373_amd import moe
+from paper_2511_11373_amd import workloads as wl
+from tests.gpu_util import check_close, check_weights, host, shape_of, to_dev, upload
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    wl.CONFIGS["tiny"],
+    wl.small_config(1, 64, 4, 2, 32, dtype=wl.BF16, seed=1, sigma_w=0.1),          # one token
+    wl.small_config(37, 72, 5, 3, 40, dtype=wl.BF16, seed=2, sigma_w=0.1),         # nothing divides a tile
+    wl.small_config(130, 264, 6, 6, 136, dtype=wl.F32, seed=3, sigma_w=0.05),      # K == E, float storage
+    wl.small_config(200, 128, 1, 1, 64, dtype=wl.BF16, seed=4, sigma_w=0.1),       # a single expert
+    wl.small_config(700, 256, 70, 4, 96, dtype=wl.BF16, seed=5, sigma_w=0.05),     # E not a multiple of 64, 2800 rows
+    wl.small_config(96, 512, 300, 8, 64, dtype=wl.BF16, seed=6, sigma_w=0.05),     # many experts, most nearly empty
+    wl.small_config(260, 256, 16, 2, 128, dtype=wl.BF16, seed=7, renormalize=False, sigma_w=0.05),
+]
+
+
+def _ids(cfgs):
+    return [c.name + ("" if c.renormalize else "-norenorm") + "-" + c.dtype for c in cfgs]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    assert torch.cuda.is_available()
+    return moe.load_library()
+
+
+def _oracle_all(oracle_lib, cfg, d):
+    idx, w = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K, d["router_bias"], cfg.renormalize)
+    off, r2a, a2r = oracle_lib.permute(idx, cfg.E)
+    return idx, w, off, r2a, a2r
+
+
+@pytest.mark.parametrize("cfg", SMALL + [wl.CONFIGS["decode64"]], ids=_ids(SMALL + [wl.CONFIGS["decode64"]]))
+def test_each_entry_point_against_oracle(lib, oracle_lib, cfg):
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+
+    # route
+    idx, w = moe.moe_route_topk(shp, g["x"], g["w_router"], g["router_bias"], ws)
+    assert np.array_equal(host(idx), o_idx)
+    check_weights(host(w), o_w)
+    if cfg.renormalize:
+        assert np.all(np.abs(host(w).astype(np.float64).sum(axis=1) - 1.0) <= 1e-6)
+
+    # permute, fed with the oracle's selection so the step is checked on its own
+    off, r2a, a2r, xp = moe.moe_permute(shp, torch.from_numpy(o_idx).cuda(), g["x"], ws)
+    assert np.array_equal(host(off), o_off)
+    assert np.array_equal(host(r2a), o_r2a)
+    assert np.array_equal(host(a2r), o_a2r)
+    o_xp = oracle_lib.gather_rows(d["x_f32"], o_r2a, cfg.K)
+    assert np.array_equal(host(xp).astype(np.float32), o_xp)
+    # permute then un-permute is the identity
+    assert torch.equal(xp[a2r.long()], g["x"].repeat_interleave(cfg.K, dim=0))
+
+    # grouped SwiGLU on the oracle's rows and offsets
+    o_y = oracle_lib.grouped_swiglu(o_xp, o_off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
+    y = moe.moe_grouped_swiglu(shp, to_dev(d["x"][o_r2a // cfg.K], cfg.dtype), torch.from_numpy(o_off).cuda(),
+                               g["w_gate"], g["w_up"], g["w_down"], ws)
+    check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
+
+    # combine on the GPU's own y_perm against the same sum in double
+    out = moe.moe_combine(shp, y, torch.from_numpy(o_a2r).cuda(), torch.from_numpy(o_w).cuda())
+    o_out_of_gpu_y = oracle_lib.combine(host(y), o_a2r, o_w)
+    check_close(host(out), o_out_of_gpu_y, "combine", max_abs=1e-2 * max(1.0, np.abs(o_out_of_gpu_y).max()), rel_l2=4e-3)
+
+    # fused forward against the oracle's forward
+    o_out = oracle_lib.combine(o_y, o_a2r, o_w)
+    idx2 = torch.empty_like(idx)
+    w2 = torch.empty_like(w)
+    out2 = moe.moe_forward(shp, g["x"], g["w_router"], g["router_bias"], g["w_gate"], g["w_up"], g["w_down"], ws,
+                           topk_idx_out=idx2, topk_w_out=w2)
+    assert np.array_equal(host(idx2), o_idx)
+    check_weights(host(w2), o_w)
+    err, rel = check_close(host(out2), o_out, "forward", max_abs=2e-2 * max(1.0, np.abs(o_out).max()))
+    assert rel <= 6e-3      # what bf16 rounding of x, W, act, y and out should cost
+    # forward without the optional outputs gives the same bits
+    out3 = moe.moe_forward(shp, g["x"], g["w_router"], g["router_bias"], g["w_gate"], g["w_up"], g["w_down"], ws)
+    assert torch.equal(out3, out2)
+
+
+def test_tie_break_and_zero_input(lib, oracle_lib):
+    cfg = wl.small_config(50, 128, 40, 8, 64, dtype=wl.BF16, seed=8, sigma_w=0.1)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    idx, w = moe.moe_route_topk(shp, g["x"], torch.zeros_like(g["w_router"]), None, ws)
+    assert np.array_equal(host(idx), np.tile(np.arange(cfg.K, dtype=np.int32), (cfg.T, 1)))
+    assert np.all(host(w) == np.float32(1.0 / cfg.K))
+    # duplicated router rows: exact ties inside every token, lower id first
+    wr = d["w_router"].copy()
+    wr[5] = wr[2]
+    wr[39] = wr[2]
+    idx, w = moe.moe_route_topk(shp, g["x"], to_dev(wr, cfg.dtype), None, ws)
+    o_idx, o_w = oracle_lib.route_topk(d["x_f32"], wl.bf16_bits_to_f32(wr), cfg.K)
+    assert np.array_equal(host(idx), o_idx)
+    out = moe.moe_forward(shp, torch.zeros_like(g["x"]), g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], ws)
+    assert torch.count_nonzero(out).item() == 0
+
+
+def test_empty_batch_and_bad_arguments(lib):
+    shp = moe.make_shape(0, 64, 4, 2, 32, moe.MOE_BF16)
+    ws = moe.alloc_workspace(shp)
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    wr = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    wg = torch.zeros((4, 32, 64), dtype=torch.bfloat16, device="cuda")
+    wd = torch.zeros((4, 64, 32), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((1, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    moe.moe_forward(shp, wr, wr, None, wg, wg, wd, ws, out=out)      # x pointer unused when T == 0
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)                                       # nothing was enqueued
+    shp = moe.make_shape(4, 64, 4, 2, 32, moe.MOE_BF16)
+    small_ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_forward(shp, wr, wr, None, wg, wg, wd, small_ws)
+    assert ei.value.code == 4
+
+
+def test_repeated_runs_are_bitwise_identical(lib):
+    cfg = wl.small_config(333, 256, 24, 4, 128, dtype=wl.BF16, seed=9, sigma_w=0.05)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    ref = None
+    for _ in range(10):
+        idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+        out = moe.moe_forward(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], ws, topk_idx_out=idx)
+        cur = (out.clone(), idx.clone())
+        if ref is None:
+            ref = cur
+        assert torch.equal(cur[0], ref[0]) and torch.equal(cur[1], ref[1])
+
+
+FULL = ["decode512", "skew4k", "prefill16k"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_forward_on_sampled_tokens(lib, oracle_lib, name):
+    """Full-size layer shapes: routing and permutation of every token are compared exactly; the block
+    output is compared on a seeded sample of tokens the oracle evaluates one by one."""
+    cfg = wl.CONFIGS[name]
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
+    out = moe.moe_forward(shp, g["x"], g["w_router"], g["router_bias"], g["w_gate"], g["w_up"], g["w_down"], ws,
+                          topk_idx_out=idx, topk_w_out=w)
+    o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+    assert np.array_equal(host(idx), o_idx)
+    check_weights(host(w), o_w)
+    off, r2a, a2r, _ = moe.moe_permute(shp, idx, g["x"], ws, want_x_perm=False)
+    assert np.array_equal(host(off), o_off) and np.array_equal(host(r2a), o_r2a) and np.array_equal(host(a2r), o_a2r)
+    rng = np.random.default_rng(123)
+    tok = np.unique(np.concatenate([[0, cfg.T - 1], rng.integers(0, cfg.T, 62)])).astype(np.int32)
+    # make sure the largest and the smallest non-empty expert are both covered
+    cnt = np.diff(o_off)
+    for e in (int(cnt.argmax()), int(np.where(cnt > 0, cnt, cnt.max() + 1).argmin())):
+        tok = np.append(tok, o_r2a[o_off[e + 1] - 1] // cfg.K).astype(np.int32)
+    ref = oracle_lib.forward_tokens(d["x_f32"], o_idx, o_w, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], tok)
+    check_close(host(out)[tok], ref, f"forward[{name}] sampled tokens")
+    assert np.all(np.isfinite(host(out)))
