@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed-expert MoE FFN block on one MI355X.
+
+One step = one moe_forward (router, permutation, grouped SwiGLU, combine) over one
+synthetic batch at the Qwen3-30B-A3B layer shape, inputs resident in HBM.  Prints
+ONE JSON line.  The default workload is the rollout decode step of 64 concurrent
+responses; --workload selects the other shapes.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode64]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+WEIGHT_SETS = 4                # expert-weight sets rotated between steps (4 x 1.2 GB > 256 MB last-level cache)
+DEFAULT_STEPS = {"tiny": 200, "decode64": 400, "decode512": 300, "prefill16k": 40, "skew4k": 100}
+HBM_BOUND = ("decode64", "decode512")
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="decode64",
+                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k"])
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                         "--gpus must be 1. See DESIGN.md for how the path would shard.\n")
+        sys.exit(2)
+    import torch
+    from paper_2511_11373_amd import moe
+    from paper_2511_11373_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(3)
+    moe.load_library()          # raises if the HIP library is not built: there is no fallback
+    cfg = wl.CONFIGS[args.workload]
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[cfg.name]
+    warmup = args.warmup if args.warmup is not None else max(5, steps // 10)
+
+    want_cpu = not args.no_cpu_baseline
+    d = wl.make_inputs(cfg, want_f32=want_cpu)
+    bf16 = cfg.dtype == wl.BF16
+    elt = 2 if bf16 else 4
+
+    def dev(a):
+        t = torch.from_numpy(a)
+        return (t.view(torch.bfloat16) if bf16 else t).cuda()
+
+    x, wr = dev(d["x"]), dev(d["w_router"])
+    bias = None if d["router_bias"] is None else torch.from_numpy(d["router_bias"]).cuda()
+    sets = [(dev(d["w_gate"]), dev(d["w_up"]), dev(d["w_down"]))]
+    for s in range(1, WEIGHT_SETS):     # equally distributed sets at other addresses: experts rotated by s
+        sets.append(tuple(torch.roll(w, shifts=s, dims=0).contiguous() for w in sets[0]))
+    shp = moe.make_shape(cfg.T, cfg.H, cfg.E, cfg.K, cfg.I, moe.MOE_BF16 if bf16 else moe.MOE_F32, cfg.renormalize)
+    ws = moe.alloc_workspace(shp)
+    out = torch.empty((cfg.T, cfg.H), dtype=x.dtype, device="cuda")
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+
+    def step(i, idx_out=None):
+        wg, wu, wd = sets[i % WEIGHT_SETS]
+        moe.moe_forward(shp, x, wr, bias, wg, wu, wd, ws, out=out, topk_idx_out=idx_out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    # realised routing (after the timed region): active experts and load histogram
+    step(0, idx_out=idx)
+    torch.cuda.synchronize()
+    load = np.bincount(idx.cpu().numpy().ravel(), minlength=cfg.E)
+    e_act = int((load > 0).sum())
+
+    # per-stage HIP-event times of the same step (the library records an event at every stage boundary)
+    stage = np.zeros(moe.NUM_STAGES)
+    n_prof = max(10, min(steps, 100))
+    for i in range(n_prof):
+        wg, wu, wd = sets[i % WEIGHT_SETS]
+        _, ms = moe.moe_forward_stage_times(shp, x, wr, bias, wg, wu, wd, ws, out=out)
+        stage += np.array(ms)
+    stage /= n_prof
+    stages_ms = {n: round(float(v), 5) for n, v in zip(moe.STAGE_NAMES, stage)}
+
+    # roofline of the dominant kernel, the gate/up GEMM (2/3 of the weight bytes and of the flops)
+    gu_ms = float(stage[moe.STAGE_NAMES.index("gate_up_gemm")])
+    gu_bytes = e_act * 2 * cfg.I * cfg.H * elt + cfg.T * cfg.H * elt + cfg.T * cfg.K * cfg.I * 2
+    gu_flops = 2.0 * cfg.T * cfg.K * 2 * cfg.I * cfg.H
+    layer_bytes = e_act * 3 * cfg.I * cfg.H * elt + cfg.E * cfg.H * elt + 2 * cfg.T * cfg.H * elt
+    layer_flops = 2.0 * cfg.T * cfg.K * 3 * cfg.I * cfg.H
+    if cfg.name in HBM_BOUND or cfg.name == "tiny":
+        ach = gu_bytes / (gu_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gate_up_gemm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "bytes_per_launch": int(gu_bytes), "avg_launch_ms": round(gu_ms, 5)}
+    else:
+        ach = gu_flops / (gu_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gate_up_gemm", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "flops_per_launch": gu_flops, "avg_launch_ms": round(gu_ms, 5)}
+    layer = {"active_experts": e_act, "load_max": int(load.max()), "load_median": float(np.median(load)),
+             "load_empty": int((load == 0).sum()),
+             "algorithmic_GB": round(layer_bytes / 1e9, 4), "algorithmic_GFLOP": round(layer_flops / 1e9, 2),
+             "hbm_frac_whole_step": round(layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+             "mfma_frac_whole_step": round(layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "stages_ms": stages_ms}
+
+    cpu = None
+    if want_cpu:
+        import oracle                      # the CPU oracle, timed as it stands: a baseline, not the target
+        xs, wrf = d["x_f32"], d["w_router_f32"]
+        wgf, wuf, wdf = d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"]
+        def run_oracle(n):
+            return oracle.forward(xs[:n], wrf, wgf, wuf, wdf, cfg.K, bias=d["router_bias"],
+                                  renormalize=cfg.renormalize)
+        n0 = min(cfg.T, 4)
+        c0 = time.perf_counter()
+        run_oracle(n0)
+        per_tok = (time.perf_counter() - c0) / n0
+        n = int(max(n0, min(cfg.T, args.cpu_seconds / max(per_tok, 1e-9))))
+        reps = int(max(1, min(1000, args.cpu_seconds / max(per_tok * n, 1e-9))))   # small batches: repeat
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            o_out, _, _ = run_oracle(n)
+        dt = time.perf_counter() - c0
+        cpu = {"value": round(n * reps / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {n} of {cfg.T} tokens of the same batch, {reps} oracle forward(s), {dt:.1f} s"}
+        # the sample doubles as a sanity check of the timed path (rows of a batch are independent)
+        step(0)
+        torch.cuda.synchronize()
+        got = out[:n].float().cpu().numpy().astype(np.float64)
+        rel = float(np.linalg.norm(got - o_out) / max(np.linalg.norm(o_out), 1e-30))
+        cpu["rel_l2_gpu_vs_oracle"] = round(rel, 6)
+
+    rec = {
+        "metric": "MoE-layer tokens/s + % HBM BW (decode) / % bf16 MFMA peak (prefill)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.E, "top_k": cfg.K,
+                   "intermediate": cfg.I, "weight_sets_rotated": WEIGHT_SETS,
+                   "router_bias": "zipf(1.2)" if cfg.zipf_s else None},
+        "roofline": roofline, "cpu_baseline": cpu, "layer": layer,
+    }
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

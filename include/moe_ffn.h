@@ -147,6 +147,21 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
                          const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
                          void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * moe_forward with a HIP event recorded on `stream` at every stage boundary, for
+ * attributing the time of one call to its kernels.  Unlike every other entry
+ * point this one blocks until the call has finished on the device.
+ *   stage_ms  host float[MOE_NUM_STAGES] out: elapsed milliseconds of
+ *             [0] router logits  [1] top-K + weights  [2] permutation (3 kernels)
+ *             [3] row-tile list  [4] gate/up GEMM + SiLU*mul  [5] down GEMM  [6] combine
+ * Same arguments, results and errors as moe_forward otherwise.
+ */
+#define MOE_NUM_STAGES 7
+moe_status_t moe_forward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router,
+                                     const float *router_bias, const void *w_gate, const void *w_up,
+                                     const void *w_down, void *out, void *ws, size_t ws_bytes,
+                                     void *stream, float *stage_ms);
+
 #ifdef __cplusplus
 }
 #endif

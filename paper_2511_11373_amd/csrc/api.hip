@@ -145,10 +145,10 @@ moe_status_t moe_combine(const moe_shape_t *shape, const void *y_perm, const int
                ? MOE_OK : MOE_ERR_HIP;
 }
 
-moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_router,
-                         const float *router_bias, const void *w_gate, const void *w_up,
-                         const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
-                         void *ws, size_t ws_bytes, void *stream) {
+static moe_status_t forward_impl(const moe_shape_t *shape, const void *x, const void *w_router,
+                                 const float *router_bias, const void *w_gate, const void *w_up,
+                                 const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                                 void *ws, size_t ws_bytes, void *stream, Probe *probe) {
     moe_status_t st = check_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !out) return MOE_ERR_NULL;
@@ -163,14 +163,50 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
     hipStream_t hs = (hipStream_t)stream;
     int32_t *idx = topk_idx_out ? topk_idx_out : w.topk_idx;
     float *tw = topk_w_out ? topk_w_out : w.topk_w;
-    if (launch_route(s, x, w_router, router_bias, w.logit_part, idx, tw, hs) != hipSuccess) return MOE_ERR_HIP;
-    if (launch_permute(s, idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
+    if (probe) { probe->st = hs; probe->mark(); }
+    if (launch_route(s, x, w_router, router_bias, w.logit_part, idx, tw, hs, probe) != hipSuccess) return MOE_ERR_HIP;
+    probe_mark(probe);
+    const bool fused_tiles = permute_is_small(s);
+    if (launch_permute(s, idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs,
+                       fused_tiles ? gemm_tile_rows(s) : 0, gemm_max_tiles(s), w.tile_map) != hipSuccess)
         return MOE_ERR_HIP;
+    probe_mark(probe);
     if (launch_grouped_swiglu(s, x, w.row_to_assign, w.expert_offsets, w_gate, w_up, w_down, w.act, w.tile_map,
-                              w.y_perm, hs) != hipSuccess)
+                              w.y_perm, hs, probe, fused_tiles) != hipSuccess)
         return MOE_ERR_HIP;
+    probe_mark(probe);
     if (launch_combine(s, w.y_perm, w.assign_to_row, tw, out, hs) != hipSuccess) return MOE_ERR_HIP;
+    probe_mark(probe);
     return MOE_OK;
+}
+
+moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_router,
+                         const float *router_bias, const void *w_gate, const void *w_up,
+                         const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                         void *ws, size_t ws_bytes, void *stream) {
+    return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out, ws,
+                        ws_bytes, stream, nullptr);
+}
+
+moe_status_t moe_forward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router,
+                                     const float *router_bias, const void *w_gate, const void *w_up,
+                                     const void *w_down, void *out, void *ws, size_t ws_bytes, void *stream,
+                                     float *stage_ms) {
+    if (!stage_ms) return MOE_ERR_NULL;
+    for (int i = 0; i < MOE_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+    if (shape && shape->T == 0) return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr, ws, ws_bytes, stream, nullptr);
+    Probe probe;
+    for (int i = 0; i <= MOE_NUM_STAGES; ++i)
+        if (hipEventCreate(&probe.ev[i]) != hipSuccess) return MOE_ERR_HIP;
+    moe_status_t st = forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr, ws,
+                                   ws_bytes, stream, &probe);
+    if (st == MOE_OK && probe.n == MOE_NUM_STAGES + 1) {
+        if (hipEventSynchronize(probe.ev[MOE_NUM_STAGES]) != hipSuccess) st = MOE_ERR_HIP;
+        for (int i = 0; i < MOE_NUM_STAGES && st == MOE_OK; ++i)
+            if (hipEventElapsedTime(&stage_ms[i], probe.ev[i], probe.ev[i + 1]) != hipSuccess) st = MOE_ERR_HIP;
+    }
+    for (int i = 0; i <= MOE_NUM_STAGES; ++i) (void)hipEventDestroy(probe.ev[i]);
+    return st;
 }
 
 }  // extern "C"

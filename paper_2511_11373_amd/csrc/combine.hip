@@ -1,5 +1,5 @@
 // Weighted combine: out[t,:] = sum_k w[t,k] * y_perm[assign_to_row[t*K+k],:], float accumulation in
-// increasing k, one rounding to the storage type.  One wave per token, 8 features per lane per step.
+// increasing k, one rounding to the storage type.
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -24,29 +24,40 @@ __device__ __forceinline__ void store8f(float *p, const float (&v)[8]) {
     *reinterpret_cast<f32x4 *>(p + 4) = b;
 }
 
+// One block per (token, slab of 2048 features); each thread owns 8 consecutive features.  The K row
+// ids and weights of a group of 8 slots are fetched first so that the 8 row loads are independent.
 template <typename S>
 __global__ __launch_bounds__(256) void combine_kernel(const S *__restrict__ y, const int32_t *__restrict__ a2r,
                                                       const float *__restrict__ w, S *__restrict__ out, int T, int H, int K) {
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= T) return;
-    const int lane = threadIdx.x & 63;
-    for (int h = lane * 8; h < H; h += 64 * 8) {
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int k = 0; k < K; ++k) {
-            const int row = a2r[(size_t)t * K + k];
-            const float wk = w[(size_t)t * K + k];
-            float v[8];
-            load8f(y + (size_t)row * H + h, v);
+    const int t = blockIdx.x;
+    const int h = (blockIdx.y * 256 + threadIdx.x) * 8;
+    if (h >= H) return;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int32_t *rows = a2r + (size_t)t * K;
+    const float *wk = w + (size_t)t * K;
+    for (int k0 = 0; k0 < K; k0 += 8) {
+        int row[8]; float wt[8]; float v[8][8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = fmaf(wk, v[j], acc[j]);
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = k0 + j < K;
+            row[j] = ok ? rows[k0 + j] : rows[0];
+            wt[j] = ok ? wk[k0 + j] : 0.f;
         }
-        store8f(out + (size_t)t * H + h, acc);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) load8f(y + (size_t)row[j] * H + h, v[j]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (k0 + j < K) {
+#pragma unroll
+                for (int f = 0; f < 8; ++f) acc[f] = fmaf(wt[j], v[j][f], acc[f]);
+            }
     }
+    store8f(out + (size_t)t * H + h, acc);
 }
 
 hipError_t launch_combine(const moe_shape_t &s, const void *y_perm, const int32_t *assign_to_row,
                           const float *topk_w, void *out, hipStream_t st) {
-    dim3 grid((s.T + 3) / 4);
+    dim3 grid(s.T, (s.H + 2047) / 2048);
     if (s.dtype == MOE_BF16)
         hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t *)y_perm, assign_to_row,
                            topk_w, (bf16_t *)out, s.T, s.H, s.K);

@@ -184,21 +184,32 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
         }
 }
 
+constexpr int kWW = 2, kWT = 2, kMW = 1, kMT = 1;      // wave grid and MFMA tiles per wave of the tiled kernel
+int gemm_tile_rows(const moe_shape_t &) { return kWT * kMT * 32; }
+int gemm_max_tiles(const moe_shape_t &s) {
+    const int n = s.T * s.K;
+    return n / gemm_tile_rows(s) + (s.E < n ? s.E : n);
+}
+
 template <typename S>
 static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int32_t *row_map,
                                const int32_t *off, const S *wg, const S *wu, const S *wd, bf16_t *act,
-                               int32_t *tile_map, S *y_perm, hipStream_t st) {
-    constexpr int WW = 2, WT = 2, MW = 1, MT = 1;
+                               int32_t *tile_map, S *y_perm, hipStream_t st, Probe *probe, bool tile_map_ready) {
+    constexpr int WW = kWW, WT = kWT, MW = kMW, MT = kMT;
     constexpr int BW = WW * MW * 32, BT = WT * MT * 32;
-    const int n = s.T * s.K;
-    const int max_tiles = n / BT + (s.E < n ? s.E : n);
-    hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, s.E, BT, max_tiles, tile_map);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    const int max_tiles = gemm_max_tiles(s);
+    hipError_t err = hipSuccess;
+    if (!tile_map_ready) {
+        hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, s.E, BT, max_tiles, tile_map);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    probe_mark(probe);
     hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT>), dim3(max_tiles, (s.I + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, x_rows, row_map, s.K, off, tile_map, max_tiles, wg, wu, act, s.H, s.I);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
+    probe_mark(probe);
     hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MW, MT>), dim3(max_tiles, (s.H + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, (const bf16_t *)act, (const int32_t *)nullptr, 1, off, tile_map,
                        max_tiles, wd, wd, y_perm, s.I, s.H);
@@ -208,12 +219,12 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
 hipError_t launch_grouped_swiglu(const moe_shape_t &s, const void *x_rows, const int32_t *row_map,
                                  const int32_t *expert_offsets, const void *w_gate, const void *w_up,
                                  const void *w_down, bf16_t *act, int32_t *tile_map, void *y_perm,
-                                 hipStream_t st) {
+                                 hipStream_t st, Probe *probe, bool tile_map_ready) {
     if (s.dtype == MOE_BF16)
         return launch_typed<bf16_t>(s, (const bf16_t *)x_rows, row_map, expert_offsets, (const bf16_t *)w_gate,
-                                    (const bf16_t *)w_up, (const bf16_t *)w_down, act, tile_map, (bf16_t *)y_perm, st);
+                                    (const bf16_t *)w_up, (const bf16_t *)w_down, act, tile_map, (bf16_t *)y_perm, st, probe, tile_map_ready);
     return launch_typed<float>(s, (const float *)x_rows, row_map, expert_offsets, (const float *)w_gate,
-                               (const float *)w_up, (const float *)w_down, act, tile_map, (float *)y_perm, st);
+                               (const float *)w_up, (const float *)w_down, act, tile_map, (float *)y_perm, st, probe, tile_map_ready);
 }
 
 }  // namespace moe

@@ -58,19 +58,35 @@ Workspace carve_workspace(const moe_shape_t &s, void *base);
 
 int router_ksplit(const moe_shape_t &s);
 
+// Optional stage timer: when given, launchers record an event at every stage boundary.
+struct Probe {
+    hipEvent_t ev[MOE_NUM_STAGES + 1];
+    int n = 0;
+    hipStream_t st = nullptr;
+    void mark() { if (n <= MOE_NUM_STAGES) (void)hipEventRecord(ev[n++], st); }
+};
+inline void probe_mark(Probe *p) { if (p) p->mark(); }
+
 // Launchers (all enqueue on `st`, return the first HIP launch error).
 hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_router, const float *bias,
-                        double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st);
+                        double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st,
+                        Probe *probe = nullptr);
+// One-block permutation is used for batches of at most 16 chunks; it can also emit the GEMM's row-tile
+// list (tile_rows > 0), which saves a launch.  Returns whether `s` takes that path.
+inline bool permute_is_small(const moe_shape_t &s) { return (long)s.T * s.K <= 16L * kPermChunk; }
 hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t *expert_offsets,
                           int32_t *row_to_assign, int32_t *assign_to_row, int32_t *chunk_base,
-                          hipStream_t st);
+                          hipStream_t st, int tile_rows = 0, int max_tiles = 0, int32_t *tile_map = nullptr);
+// Row-tile geometry of the grouped GEMM that launch_grouped_swiglu will pick for `s`.
+int gemm_tile_rows(const moe_shape_t &s);
+int gemm_max_tiles(const moe_shape_t &s);
 hipError_t launch_gather_rows(const moe_shape_t &s, const void *x, const int32_t *row_to_assign,
                               void *x_perm, hipStream_t st);
 // x_rows: either x_perm (row_map == nullptr) or x with row_map = row_to_assign (row r reads x[row_map[r]/K]).
 hipError_t launch_grouped_swiglu(const moe_shape_t &s, const void *x_rows, const int32_t *row_map,
                                  const int32_t *expert_offsets, const void *w_gate, const void *w_up,
                                  const void *w_down, bf16_t *act, int32_t *tile_map, void *y_perm,
-                                 hipStream_t st);
+                                 hipStream_t st, Probe *probe = nullptr, bool tile_map_ready = false);
 hipError_t launch_combine(const moe_shape_t &s, const void *y_perm, const int32_t *assign_to_row,
                           const float *topk_w, void *out, hipStream_t st);
 

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__rest
     const int a0 = chunk * kPermChunk;
     if (a0 < n) {
         const int a1 = min(a0 + kPermChunk, n);
-        for (int a = a0 + lane; a < a1; a += 64) atomicAdd(&hist[idx[a]], 1);   // counts: order free
+        for (int a = a0 + lane; a < a1; a += 64) atomicAdd(&hist[min(max(idx[a], 0), E - 1)], 1);   // counts: order free
     }
     __syncthreads();
     if (a0 < n)
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const int32_t *__r
     for (int ab = a0; ab < a1; ab += 64) {
         const int a = ab + lane;
         const bool live = a < a1;
-        const int e = live ? idx[a] : 0;
+        const int e = live ? min(max(idx[a], 0), E - 1) : 0;
         unsigned long long peers = __ballot(live);
         for (int b = 0; b < ebits; ++b) {
             const unsigned long long has = __ballot((e >> b) & 1);
@@ -102,6 +102,98 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const int32_t *__r
         if (live) {
             const int rank = __popcll(peers & below);
             const int row = next_row[e] + rank;
+            row_to_assign[row] = a;
+            assign_to_row[a] = row;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (live && (peers & below) == 0ull) next_row[e] = next_row[e] + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- small batches: the whole permutation (and the GEMM's row-tile list) in one block --------------
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+// Exclusive scan of one value per thread over a 1024-thread block; *total receives the sum.
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wave_sums /* [17] shared */, int *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int inc = wave_inclusive_scan(v, lane);
+    __syncthreads();                       // wave_sums may still be read from a previous call
+    if (lane == 63) wave_sums[wave] = inc;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_sums[w];
+    if (threadIdx.x == 1023) *total = before + inc;
+    return before + inc - v;
+}
+
+// n <= 16 * kPermChunk assignments.  Wave w owns chunk w.  Same three steps as the large path with
+// the histograms kept in LDS.  With tile_rows > 0 it also writes the list of (expert, first row) row
+// tiles that the grouped GEMM consumes: tile_map[2*i], tile_map[2*i+1], count at tile_map[2*max_tiles].
+__global__ __launch_bounds__(1024) void permute_small_kernel(const int32_t *__restrict__ idx, int n, int E, int ebits,
+                                                             int32_t *__restrict__ expert_offsets,
+                                                             int32_t *__restrict__ row_to_assign,
+                                                             int32_t *__restrict__ assign_to_row, int tile_rows,
+                                                             int max_tiles, int32_t *__restrict__ tile_map) {
+    extern __shared__ int lds[];            // [16][E] per-wave counts, then per-wave next free row
+    __shared__ int offs[kMaxExperts + 1];
+    __shared__ int wave_sums[17];
+    __shared__ int total;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < 16 * E; i += 1024) lds[i] = 0;
+    __syncthreads();
+    const int a0 = wave * kPermChunk, a1 = min(a0 + kPermChunk, n);
+    int *mine = lds + (size_t)wave * E;
+    for (int a = a0 + lane; a < a1; a += 64) atomicAdd(&mine[min(max(idx[a], 0), E - 1)], 1);
+    __syncthreads();
+    // per expert: running sum over the 16 waves -> rows of e in earlier chunks; total per expert
+    int cnt = 0;
+    if ((int)threadIdx.x < E) {
+        for (int w = 0; w < 16; ++w) { const int v = lds[w * E + threadIdx.x]; lds[w * E + threadIdx.x] = cnt; cnt += v; }
+    }
+    const int first = block_exclusive_scan(cnt, wave_sums, &total);      // E <= 1024 = blockDim
+    if ((int)threadIdx.x < E) {
+        offs[threadIdx.x] = first;
+        expert_offsets[threadIdx.x] = first;
+        for (int w = 0; w < 16; ++w) lds[w * E + threadIdx.x] += first;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { offs[E] = total; expert_offsets[E] = total; }
+    // row tiles
+    if (tile_rows > 0) {
+        const int nt = (int)threadIdx.x < E ? (cnt + tile_rows - 1) / tile_rows : 0;
+        int tile_total;
+        int *tt = &wave_sums[16];
+        const int t0 = block_exclusive_scan(nt, wave_sums, tt);
+        for (int i = 0; i < nt && t0 + i < max_tiles; ++i) {
+            tile_map[2 * (t0 + i)] = threadIdx.x;
+            tile_map[2 * (t0 + i) + 1] = first + i * tile_rows;
+        }
+        __syncthreads();
+        tile_total = *tt;
+        if (threadIdx.x == 0) tile_map[2 * max_tiles] = tile_total < max_tiles ? tile_total : max_tiles;
+    }
+    __syncthreads();
+    // stable scatter, one wave per chunk
+    volatile int *next_row = mine;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int ab = a0; ab < a1; ab += 64) {
+        const int a = ab + lane;
+        const bool live = a < a1;
+        const int e = live ? min(max(idx[a], 0), E - 1) : 0;
+        unsigned long long peers = __ballot(live);
+        for (int b = 0; b < ebits; ++b) {
+            const unsigned long long has = __ballot((e >> b) & 1);
+            peers &= ((e >> b) & 1) ? has : ~has;
+        }
+        if (live) {
+            const int row = next_row[e] + __popcll(peers & below);
             row_to_assign[row] = a;
             assign_to_row[a] = row;
         }
@@ -123,8 +215,15 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const u32x4 *__restric
 
 hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t *expert_offsets,
                           int32_t *row_to_assign, int32_t *assign_to_row, int32_t *chunk_base,
-                          hipStream_t st) {
+                          hipStream_t st, int tile_rows, int max_tiles, int32_t *tile_map) {
     const int n = s.T * s.K;
+    int ebits = 0;
+    while ((1 << ebits) < s.E) ++ebits;
+    if (permute_is_small(s)) {
+        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(1024), (size_t)16 * s.E * sizeof(int), st, topk_idx, n,
+                           s.E, ebits, expert_offsets, row_to_assign, assign_to_row, tile_rows, max_tiles, tile_map);
+        return hipGetLastError();
+    }
     const int nchunks = (n + kPermChunk - 1) / kPermChunk;
     const size_t smem = (size_t)4 * s.E * sizeof(int);
     dim3 grid((nchunks + 3) / 4);
@@ -134,8 +233,6 @@ hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, chunk_base, nchunks, s.E, expert_offsets);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
-    int ebits = 0;
-    while ((1 << ebits) < s.E) ++ebits;
     hipLaunchKernelGGL(permute_scatter_kernel, grid, dim3(256), smem, st, topk_idx, n, s.E, ebits, chunk_base,
                        row_to_assign, assign_to_row);
     return hipGetLastError();

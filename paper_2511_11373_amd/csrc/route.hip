@@ -97,10 +97,39 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     }
     return v;
 }
-__device__ __forceinline__ double wave_sum_f64(double v) {
+__device__ __forceinline__ float wave_sum_f32(float v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
     return v;
+}
+
+// logit of (t, e): the partial sums of the k splits added in split order, plus the bias, in double,
+// rounded once to float.
+__device__ __forceinline__ float final_logit(const double *__restrict__ part, int ksplit, size_t split_stride,
+                                             size_t pos, const float *__restrict__ bias, int e) {
+    double s = 0.0;
+    int z = 0;
+    for (; z + 4 <= ksplit; z += 4) {
+        const double a = part[pos + (size_t)z * split_stride], b = part[pos + (size_t)(z + 1) * split_stride];
+        const double c = part[pos + (size_t)(z + 2) * split_stride], d = part[pos + (size_t)(z + 3) * split_stride];
+        s = (((s + a) + b) + c) + d;
+    }
+    for (; z < ksplit; ++z) s += part[pos + (size_t)z * split_stride];
+    if (bias) s += (double)bias[e];
+    return (float)s;
+}
+
+// Weights from the selected logits sel[0..K) (descending) of one token; all lanes of the wave call it.
+__device__ __forceinline__ void write_weights(const float *sel, int K, int renorm, float denom_all,
+                                              float *__restrict__ dst, int lane) {
+    const float m = sel[0];
+    float denom = denom_all;
+    if (renorm) {
+        float part_sum = 0.f;
+        for (int k = lane; k < K; k += 64) part_sum += expf(sel[k] - m);
+        denom = wave_sum_f32(part_sum);
+    }
+    for (int k = lane; k < K; k += 64) dst[k] = expf(sel[k] - m) / denom;
 }
 
 // One wave per token.  Lane l holds the logits of experts l, l+64, ...  Each of the K rounds takes
@@ -119,12 +148,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const double *__restrict__ pa
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
-        double s = 0.0;
-        if (e < E) {
-            for (int z = 0; z < ksplit; ++z) s += part[((size_t)z * T + t) * E + e];
-            if (bias) s += (double)bias[e];
-        }
-        logit[r] = (float)s;
+        logit[r] = e < E ? final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e) : 0.f;
     }
     unsigned int taken = 0;
     for (int k = 0; k < K; ++k) {
@@ -149,17 +173,75 @@ __global__ __launch_bounds__(256) void topk_kernel(const double *__restrict__ pa
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const double m = (double)sel[0];
-    double denom = 0.0;
-    if (renorm) {
-        for (int k = lane; k < K; k += 64) denom += exp((double)sel[k] - m);
-    } else {
+    float denom_all = 0.f;
+    if (!renorm) {
+        const float m = sel[0];
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            if (lane + 64 * r < E) denom += exp((double)logit[r] - m);
+            if (lane + 64 * r < E) denom_all += expf(logit[r] - m);
+        denom_all = wave_sum_f32(denom_all);
     }
-    denom = wave_sum_f64(denom);
-    for (int k = lane; k < K; k += 64) topk_w[(size_t)t * K + k] = (float)(exp((double)sel[k] - m) / denom);
+    write_weights(sel, K, renorm, denom_all, topk_w + (size_t)t * K, lane);
+}
+
+// Same result for E <= 64*R <= 256 without a serial chain: every lane counts, for each of its
+// logits, how many (logit, id) pairs of the token precede it; that count is its slot.
+template <int R>
+__global__ __launch_bounds__(256) void topk_rank_kernel(const double *__restrict__ part, int ksplit,
+                                                        const float *__restrict__ bias, int32_t *__restrict__ topk_idx,
+                                                        float *__restrict__ topk_w, int T, int E, int K, int renorm) {
+    __shared__ __attribute__((aligned(16))) unsigned int keys_all[4][R * 64];
+    __shared__ float sel_all[4][R * 64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= T) return;
+    unsigned int *keys = keys_all[wave];
+    float *sel = sel_all[wave];
+    float logit[R];
+    unsigned int key[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int e = lane + 64 * r;
+        logit[r] = e < E ? final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e) : 0.f;
+        key[r] = e < E ? float_order_bits(logit[r]) : 0u;     // 0 sorts below every finite float
+        keys[e] = key[r];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    int rank[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rank[r] = 0;
+    for (int e4 = 0; e4 < R * 64; e4 += 4) {
+        const u32x4 k4 = *reinterpret_cast<const u32x4 *>(&keys[e4]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int e = lane + 64 * r;
+                rank[r] += (k4[j] > key[r]) || (k4[j] == key[r] && (e4 + j) < e);
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int e = lane + 64 * r;
+        if (e < E && rank[r] < K) {
+            topk_idx[(size_t)t * K + rank[r]] = e;
+            sel[rank[r]] = logit[r];
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float denom_all = 0.f;
+    if (!renorm) {
+        const float m = sel[0];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (lane + 64 * r < E) denom_all += expf(logit[r] - m);
+        denom_all = wave_sum_f32(denom_all);
+    }
+    write_weights(sel, K, renorm, denom_all, topk_w + (size_t)t * K, lane);
 }
 
 int router_ksplit(const moe_shape_t &s) {
@@ -173,7 +255,7 @@ int router_ksplit(const moe_shape_t &s) {
 }
 
 hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_router, const float *bias,
-                        double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st) {
+                        double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st, Probe *probe) {
     const int ks = router_ksplit(s);
     const int nchunks = (s.H + 31) / 32;
     const int cps = (nchunks + ks - 1) / ks;
@@ -187,6 +269,7 @@ hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_route
                            (const float *)w_router, logit_part, s.T, s.H, s.E, cps);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
+    probe_mark(probe);
 
     dim3 g2((s.T + 3) / 4);
     const size_t smem = (size_t)4 * s.K * sizeof(float);
@@ -194,9 +277,13 @@ hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_route
 #define MOE_TOPK(RR)                                                                                   \
     hipLaunchKernelGGL(topk_kernel<RR>, g2, dim3(256), smem, st, logit_part, ks, bias, topk_idx, topk_w, \
                        s.T, s.E, s.K, s.renormalize)
-    if (r <= 1) MOE_TOPK(1);
-    else if (r <= 2) MOE_TOPK(2);
-    else if (r <= 4) MOE_TOPK(4);
+#define MOE_TOPK_RANK(RR)                                                                              \
+    hipLaunchKernelGGL(topk_rank_kernel<RR>, g2, dim3(256), 0, st, logit_part, ks, bias, topk_idx, topk_w, \
+                       s.T, s.E, s.K, s.renormalize)
+    if (r <= 1) MOE_TOPK_RANK(1);
+    else if (r <= 2) MOE_TOPK_RANK(2);
+    else if (r <= 4) MOE_TOPK_RANK(4);
+#undef MOE_TOPK_RANK
     else if (r <= 8) MOE_TOPK(8);
     else MOE_TOPK(16);
 #undef MOE_TOPK

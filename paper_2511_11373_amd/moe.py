@@ -18,7 +18,9 @@ LIB_PATH = os.path.join(_PKG, "libmoe_ffn.so")
 
 MOE_BF16, MOE_F32 = 0, 1
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_topk", "moe_permute",
-           "moe_grouped_swiglu", "moe_combine", "moe_forward")
+           "moe_grouped_swiglu", "moe_combine", "moe_forward", "moe_forward_stage_times")
+NUM_STAGES = 7
+STAGE_NAMES = ("router_logits", "topk", "permute", "tile_list", "gate_up_gemm", "down_gemm", "combine")
 
 
 class MoeShape(ctypes.Structure):
@@ -52,6 +54,8 @@ def load_library() -> ctypes.CDLL:
         lib.moe_grouped_swiglu.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp]
         lib.moe_forward.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_forward_stage_times.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
+                                                ctypes.POINTER(ctypes.c_float)]
         for name in EXPORTS[1:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -138,3 +142,14 @@ def moe_forward(shape: MoeShape, x, w_router, router_bias, w_gate, w_up, w_down,
                                       _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(topk_idx_out), _ptr(topk_w_out),
                                       _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+def moe_forward_stage_times(shape: MoeShape, x, w_router, router_bias, w_gate, w_up, w_down, ws, out=None):
+    """moe_forward with per-stage event timing; blocks. Returns (out, [ms per stage])."""
+    if out is None:
+        out = torch.empty((shape.T, shape.H), dtype=x.dtype, device=x.device)
+    ms = (ctypes.c_float * NUM_STAGES)()
+    _check(load_library().moe_forward_stage_times(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias),
+                                                  _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(ws),
+                                                  ws.numel(), _stream(), ms))
+    return out, [float(v) for v in ms]
