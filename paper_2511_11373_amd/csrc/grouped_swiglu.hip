@@ -184,8 +184,16 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
         }
 }
 
+// large-batch bf16 variant (grouped_swiglu_big.hip)
+bool big_gemm_applicable(const moe_shape_t &s);
+int big_tile_rows();
+hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
+                                     const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
+                                     bf16_t *act, const int32_t *tile_map, int max_tiles, bf16_t *y_perm,
+                                     hipStream_t st, Probe *probe);
+
 constexpr int kWW = 2, kWT = 2, kMW = 1, kMT = 1;      // wave grid and MFMA tiles per wave of the tiled kernel
-int gemm_tile_rows(const moe_shape_t &) { return kWT * kMT * 32; }
+int gemm_tile_rows(const moe_shape_t &s) { return big_gemm_applicable(s) ? big_tile_rows() : kWT * kMT * 32; }
 int gemm_max_tiles(const moe_shape_t &s) {
     const int n = s.T * s.K;
     return n / gemm_tile_rows(s) + (s.E < n ? s.E : n);
@@ -200,11 +208,15 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
     const int max_tiles = gemm_max_tiles(s);
     hipError_t err = hipSuccess;
     if (!tile_map_ready) {
-        hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, s.E, BT, max_tiles, tile_map);
+        hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, s.E, gemm_tile_rows(s), max_tiles, tile_map);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
     probe_mark(probe);
+    if constexpr (sizeof(S) == 2) {
+        if (big_gemm_applicable(s))
+            return launch_grouped_swiglu_big(s, x_rows, row_map, off, wg, wu, wd, act, tile_map, max_tiles, y_perm, st, probe);
+    }
     hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT>), dim3(max_tiles, (s.I + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, x_rows, row_map, s.K, off, tile_map, max_tiles, wg, wu, act, s.H, s.I);
     err = hipGetLastError();

@@ -1,0 +1,275 @@
+// Large-batch grouped GEMM for bf16 storage: 256 weight rows x 256 token rows per block, direct
+// global->LDS loads (no register staging), two LDS stages, 32x32x16 bf16 MFMA.
+//
+// Block = 4 waves in a 2 (weight) x 2 (token) grid; a wave owns 4 weight tiles x 4 token tiles of
+// 32x32, i.e. 16 accumulators (256 VGPRs).  For the gate/up pass the 256 weight rows are 128 rows of
+// Wg and the same 128 rows of Wu, so that silu(g)*u is formed in registers.
+//
+// LDS stage layout (per operand): 256 rows x 128 bytes (64 bf16 of the reduction axis), dense.
+// A global_load_lds_dwordx4 writes 64 lanes x 16 B = 8 rows contiguously; to keep the later MFMA
+// operand reads (ds_read_b128 by 16 consecutive rows at the same k) off the same banks, the 16-byte
+// piece j of row r is stored at position j ^ ((r >> 1) & 7) of the row; the lane that fills a
+// position fetches the matching piece from global memory, so every 8 lanes still read one full
+// 128-byte line.
+//
+// Row tiles are walked in a list (expert, first row); the flattened (row tile, weight tile) index is
+// remapped so that each XCD (blocks are dealt round-robin to the 8 XCDs) works on a contiguous range
+// of the list: the blocks that share an expert's weights and a row tile's tokens share one L2.
+#include "moe_internal.hpp"
+
+namespace moe {
+
+namespace big {
+constexpr int BW = 256, BT = 256, BK = 64;
+constexpr int ROWB = BK * 2;                  // bytes per LDS row
+constexpr int OPB = 256 * ROWB;               // bytes per operand stage (32 KB)
+}  // namespace big
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void gbl_void;
+
+// The compiler tracks LDS writes made by global_load_lds conservatively: an ordinary LDS read that
+// follows would wait for every load in flight, including the next stage's.  The MFMA operand reads of
+// the main loop are therefore issued as inline asm and the counters are waited on by hand:
+//   vmcnt   - global->LDS loads of this wave (complete in order)
+//   lgkmcnt - LDS reads of this wave (complete in order)
+// The wait that guards a set of operand registers names them as in/out operands so that the MFMAs
+// consuming them cannot be scheduled above it.
+#define MOE_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
+
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr, int) = delete;
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lds_reads(bf16x8 (&a)[4], bf16x8 (&b)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3])
+                 : "n"(N)
+                 : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr(const void *p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) void *)p;
+}
+
+__device__ __forceinline__ float silu_mul_f(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+template <bool GATE_UP>
+__global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
+    const bf16_t *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
+    const int32_t *__restrict__ off, const int32_t *__restrict__ tile_map, int max_tiles,
+    const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1, bf16_t *__restrict__ outp, int KD, int NW,
+    int n_wtiles) {
+    using namespace big;
+    __shared__ __attribute__((aligned(1024))) unsigned char WsA[OPB];
+    __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
+    __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
+    __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
+
+    // ---- which tile --------------------------------------------------------------------------
+    const int total = tile_map[2 * max_tiles] * n_wtiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = blockIdx.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || logical >= total) return;
+    const int rtile = logical / n_wtiles, wtile = logical - rtile * n_wtiles;
+    const int e = tile_map[2 * rtile], row0 = tile_map[2 * rtile + 1];
+    const int row_end = off[e + 1];
+    const int wrow0 = wtile * (GATE_UP ? BW / 2 : BW);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ww = wave & 1, wt = wave >> 1;
+
+    // ---- global sources of this thread's 8 + 8 pieces per stage ---------------------------------
+    // load instruction i of this wave fills LDS rows (i*4 + wave)*8 .. +8; lane -> (row lane/8, position lane%8).
+    // (row >> 1) & 7 does not depend on i, so neither does the piece a lane fetches.
+    const int lrow = wave * 8 + (lane >> 3);                      // LDS row of instruction 0
+    const int piece = (lane & 7) ^ ((lrow >> 1) & 7);
+    // weights: rows are a fixed stride apart (the launcher guarantees whole weight tiles)
+    const bf16_t *wbase0 = w0 + ((size_t)e * NW + wrow0 + lrow) * KD + piece * 8;
+    const bf16_t *wbase1 = GATE_UP ? w1 + ((size_t)e * NW + wrow0 + lrow) * KD + piece * 8 : wbase0;
+    const size_t wstride = (size_t)32 * KD;
+    // token rows: gathered, clamped to the expert's last row (results of clamped rows are never stored)
+    int xrow[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int xr = row0 + i * 32 + lrow;
+        xr = xr < row_end ? xr : row_end - 1;
+        xrow[i] = row_map ? row_map[xr] / K_assign : xr;
+    }
+    const bf16_t *xbase = xrows + piece * 8;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    auto issue = [&](unsigned char *Ws, unsigned char *Xs, int k0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const bf16_t *wp = GATE_UP ? (i < 4 ? wbase0 + i * wstride : wbase1 + (i - 4) * wstride) : wbase0 + i * wstride;
+            __builtin_amdgcn_global_load_lds((gbl_void *)(wp + k0), (lds_void *)(Ws + (i * 4 + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_void *)(xbase + (size_t)xrow[i] * KD + k0),
+                                             (lds_void *)(Xs + (i * 4 + wave) * 1024), 16, 0, 0);
+        }
+    };
+    // operand addresses inside a stage: lane (row l%32, half l/32); k step ks uses pieces 2*ks + half.
+    // Tile bases are multiples of 32 rows, so the swizzle term only depends on the lane.
+    const int orow = lane & 31, ohalf = lane >> 5, sw = (orow >> 1) & 7;
+    unsigned kpos[BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) kpos[ks] = orow * ROWB + (((2 * ks + ohalf) ^ sw) << 4);
+    const unsigned a_base = (GATE_UP ? ww * 64 : ww * 128) * ROWB;
+    const unsigned b_base = wt * 128 * ROWB;
+    constexpr int A1 = GATE_UP ? 32 * ROWB : 32 * ROWB, A2 = GATE_UP ? 128 * ROWB : 64 * ROWB,
+                  A3 = GATE_UP ? 160 * ROWB : 96 * ROWB;
+    bf16x8 aop[2][4], bop[2][4];
+    auto read_ops = [&](unsigned ws, unsigned xs, int ks, int set) {
+        const unsigned wa = ws + a_base + kpos[ks], xa = xs + b_base + kpos[ks];
+        aop[set][0] = lds_read_b128<0>(wa);
+        bop[set][0] = lds_read_b128<0>(xa);
+        bop[set][1] = lds_read_b128<32 * ROWB>(xa);
+        aop[set][1] = lds_read_b128<A1>(wa);
+        bop[set][2] = lds_read_b128<64 * ROWB>(xa);
+        bop[set][3] = lds_read_b128<96 * ROWB>(xa);
+        aop[set][2] = lds_read_b128<A2>(wa);
+        aop[set][3] = lds_read_b128<A3>(wa);
+    };
+    auto mfma16 = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+    };
+
+    // ---- main loop ------------------------------------------------------------------------------------
+    // Two LDS stages.  While stage kt is multiplied, the loads of stage kt+1 (issued a whole stage earlier)
+    // land in the other buffer; operand registers are double-buffered per 16-wide k step.
+    const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
+    const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
+    issue(WsA, XsA, 0);
+    if (nk > 1) { issue(WsB, XsB, BK); MOE_WAIT_VMCNT(16); } else { MOE_WAIT_VMCNT(0); }
+    __builtin_amdgcn_s_barrier();
+    read_ops(wsA, xsA, 0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const bool odd = kt & 1;
+        const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
+        const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
+        read_ops(wcur, xcur, 1, 1);
+        wait_lds_reads<8>(aop[0], bop[0]);
+        mfma16(0);
+        read_ops(wcur, xcur, 2, 0);
+        wait_lds_reads<8>(aop[1], bop[1]);
+        mfma16(1);
+        read_ops(wcur, xcur, 3, 1);
+        wait_lds_reads<8>(aop[0], bop[0]);
+        mfma16(0);
+        wait_lds_reads<0>(aop[1], bop[1]);       // every read of the current stage has landed
+        __builtin_amdgcn_s_barrier();            // ... in every wave: the buffer may be refilled
+        if (kt + 2 < nk) {
+            if (odd) issue(WsB, XsB, (kt + 2) * BK); else issue(WsA, XsA, (kt + 2) * BK);
+            MOE_WAIT_VMCNT(16);                  // stage kt+1 (issued one stage ago) has landed
+        } else {
+            MOE_WAIT_VMCNT(0);
+        }
+        if (kt + 1 < nk) {
+            __builtin_amdgcn_s_barrier();        // ... in every wave
+            read_ops(wnxt, xnxt, 0, 0);
+        }
+        mfma16(1);
+    }
+    __builtin_amdgcn_s_barrier();
+
+    // ---- epilogue -----------------------------------------------------------------------------------
+    if (GATE_UP) {
+        // Raw g and u accumulators go through this wave's 32 KB of LDS (the stage buffers are free now) and
+        // come back paired, 8 consecutive features of one token per lane: silu(g)*u is formed there and
+        // stored as 16-byte pieces, 128 contiguous bytes per token row.
+        unsigned char *region = wave == 0 ? WsA : wave == 1 ? XsA : wave == 2 ? WsB : XsB;
+        constexpr int TROW = 32 * 4 + 16;                    // bytes per token row of a 32x32 float tile (padded)
+        constexpr int TILEB = 32 * TROW;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
+                    *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int n = p * 8 + (lane >> 3);            // token inside the 32-token tile
+                const int c = lane & 7;                       // 8-feature piece of the wave's 64 features
+                const int at = c >> 2, fi = (c & 3) * 8;      // tile (0/1) and first feature inside it
+                const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
+                const unsigned char *up = gp + 2 * TILEB;
+                const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gp), g1 = *reinterpret_cast<const f32x4 *>(gp + 16);
+                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(up), u1 = *reinterpret_cast<const f32x4 *>(up + 16);
+                const int row = row0 + wt * 128 + b * 32 + n;
+                const int f = wrow0 + ww * 64 + c * 8;
+                if (row < row_end && f < NW) {
+                    u32x4 pk = {pack_bf16x2(silu_mul_f(g0[0], u0[0]), silu_mul_f(g0[1], u0[1])),
+                                pack_bf16x2(silu_mul_f(g0[2], u0[2]), silu_mul_f(g0[3], u0[3])),
+                                pack_bf16x2(silu_mul_f(g1[0], u1[0]), silu_mul_f(g1[1], u1[1])),
+                                pack_bf16x2(silu_mul_f(g1[2], u1[2]), silu_mul_f(g1[3], u1[3]))};
+                    *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int row = row0 + wt * 128 + b * 32 + (lane & 31);
+            if (row >= row_end) continue;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int f = wrow0 + ww * 128 + a * 32 + 8 * rq + 4 * (lane >> 5);
+                    if (f >= NW) continue;
+                    u32x2 pk = {pack_bf16x2(acc[a][b][4 * rq], acc[a][b][4 * rq + 1]),
+                                pack_bf16x2(acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3])};
+                    *reinterpret_cast<u32x2 *>(outp + (size_t)row * NW + f) = pk;
+                }
+        }
+    }
+}
+
+bool big_gemm_applicable(const moe_shape_t &s) {
+    // whole weight tiles in both passes, whole k tiles, and enough rows per expert to fill 256-row tiles
+    return s.dtype == MOE_BF16 && s.H % big::BW == 0 && s.I % (big::BW / 2) == 0 && (long)s.T * s.K >= 128L * s.E;
+}
+int big_tile_rows() { return big::BT; }
+
+hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
+                                     const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
+                                     bf16_t *act, const int32_t *tile_map, int max_tiles, bf16_t *y_perm,
+                                     hipStream_t st, Probe *probe) {
+    using namespace big;
+    const int nw1 = (s.I + BW / 2 - 1) / (BW / 2), nw2 = (s.H + BW - 1) / BW;
+    const int g1 = ((max_tiles * nw1 + 7) / 8) * 8, g2 = ((max_tiles * nw2 + 7) / 8) * 8;
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<true>, dim3(g1), dim3(256), 0, st, x_rows, row_map, s.K, off, tile_map,
+                       max_tiles, wg, wu, act, s.H, s.I, nw1);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    probe_mark(probe);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(g2), dim3(256), 0, st, (const bf16_t *)act,
+                       (const int32_t *)nullptr, 1, off, tile_map, max_tiles, wd, wd, y_perm, s.I, s.H, nw2);
+    return hipGetLastError();
+}
+
+}  // namespace moe
