@@ -68,6 +68,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
+    __shared__ __attribute__((aligned(256))) unsigned char Sink[4 * 512];   // landing area of the L2 warm-up loads
 
     // ---- which tile --------------------------------------------------------------------------
     const int total = tile_map[2 * max_tiles] * n_wtiles;
@@ -82,6 +83,10 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ww = wave & 1, wt = wave >> 1;
+    // The 256 token rows are 8 sub-tiles of 32; token-wave wt owns sub-tiles wt, wt+2, wt+4, wt+6, so a
+    // short (ragged) tile is split evenly between the two token waves.  nb = live sub-tiles of this wave.
+    const int nsub = min(8, (row_end - row0 + 31) >> 5);
+    const int nb = max(0, min(4, (nsub - wt + 1) >> 1));
 
     // ---- global sources of this thread's 8 + 8 pieces per stage ---------------------------------
     // load instruction i of this wave fills LDS rows (i*4 + wave)*8 .. +8; lane -> (row lane/8, position lane%8).
@@ -101,6 +106,16 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
         xrow[i] = row_map ? row_map[xr] / K_assign : xr;
     }
     const bf16_t *xbase = xrows + piece * 8;
+    // L2 warm-up: one 128-byte line of a later stage per thread and operand (row (lane%8)*32 + lrow)
+    const bf16_t *pf_w, *pf_x;
+    {
+        const int prow = (lane & 7) * 32 + lrow;
+        if (GATE_UP) pf_w = (prow < 128 ? w0 : w1) + ((size_t)e * NW + wrow0 + (prow & 127)) * KD;
+        else pf_w = w0 + ((size_t)e * NW + wrow0 + prow) * KD;
+        int xr = row0 + prow;
+        xr = xr < row_end ? xr : row_end - 1;
+        pf_x = xrows + (size_t)(row_map ? row_map[xr] / K_assign : xr) * KD;
+    }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -119,6 +134,12 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                                              (lds_void *)(Xs + (i * 4 + wave) * 1024), 16, 0, 0);
         }
     };
+    const int k_last = KD - BK;
+    auto warm = [&](int k0) {        // two 4-byte loads per thread whose only purpose is to pull lines into L2
+        k0 = k0 < k_last ? k0 : k_last;
+        __builtin_amdgcn_global_load_lds((gbl_void *)(pf_w + k0), (lds_void *)(Sink + wave * 512), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_void *)(pf_x + k0), (lds_void *)(Sink + wave * 512 + 256), 4, 0, 0);
+    };
     // operand addresses inside a stage: lane (row l%32, half l/32); k step ks uses pieces 2*ks + half.
     // Tile bases are multiples of 32 rows, so the swizzle term only depends on the lane.
     const int orow = lane & 31, ohalf = lane >> 5, sw = (orow >> 1) & 7;
@@ -126,36 +147,47 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) kpos[ks] = orow * ROWB + (((2 * ks + ohalf) ^ sw) << 4);
     const unsigned a_base = (GATE_UP ? ww * 64 : ww * 128) * ROWB;
-    const unsigned b_base = wt * 128 * ROWB;
-    constexpr int A1 = GATE_UP ? 32 * ROWB : 32 * ROWB, A2 = GATE_UP ? 128 * ROWB : 64 * ROWB,
-                  A3 = GATE_UP ? 160 * ROWB : 96 * ROWB;
+    const unsigned b_base = wt * 32 * ROWB;
+    constexpr int A1 = 32 * ROWB, A2 = GATE_UP ? 128 * ROWB : 64 * ROWB, A3 = GATE_UP ? 160 * ROWB : 96 * ROWB;
     bf16x8 aop[2][4], bop[2][4];
     auto read_ops = [&](unsigned ws, unsigned xs, int ks, int set) {
         const unsigned wa = ws + a_base + kpos[ks], xa = xs + b_base + kpos[ks];
         aop[set][0] = lds_read_b128<0>(wa);
         bop[set][0] = lds_read_b128<0>(xa);
-        bop[set][1] = lds_read_b128<32 * ROWB>(xa);
+        bop[set][1] = lds_read_b128<64 * ROWB>(xa);
         aop[set][1] = lds_read_b128<A1>(wa);
-        bop[set][2] = lds_read_b128<64 * ROWB>(xa);
-        bop[set][3] = lds_read_b128<96 * ROWB>(xa);
+        bop[set][2] = lds_read_b128<128 * ROWB>(xa);
+        bop[set][3] = lds_read_b128<192 * ROWB>(xa);
         aop[set][2] = lds_read_b128<A2>(wa);
         aop[set][3] = lds_read_b128<A3>(wa);
     };
     auto mfma16 = [&](int set) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b)
+            if (b < nb) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+                for (int a = 0; a < 4; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+            }
     };
 
     // ---- main loop ------------------------------------------------------------------------------------
     // Two LDS stages.  While stage kt is multiplied, the loads of stage kt+1 (issued a whole stage earlier)
-    // land in the other buffer; operand registers are double-buffered per 16-wide k step.
+    // land in the other buffer; operand registers are double-buffered per 16-wide k step.  Lines of stage
+    // kt+4 are pulled into L2 two stages before their real load is issued.
+    // Loads retire in order; between the loads of stage kt+1 and the wait for them lie 2 warm-up loads, the 16
+    // loads of stage kt+2 and 2 more warm-up loads: vmcnt(20).
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
     issue(WsA, XsA, 0);
-    if (nk > 1) { issue(WsB, XsB, BK); MOE_WAIT_VMCNT(16); } else { MOE_WAIT_VMCNT(0); }
+    if (nk > 1) {
+        issue(WsB, XsB, BK);
+        warm(2 * BK);
+        warm(3 * BK);
+        MOE_WAIT_VMCNT(20);
+    } else {
+        MOE_WAIT_VMCNT(0);
+    }
     __builtin_amdgcn_s_barrier();
     read_ops(wsA, xsA, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
@@ -175,7 +207,8 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
         __builtin_amdgcn_s_barrier();            // ... in every wave: the buffer may be refilled
         if (kt + 2 < nk) {
             if (odd) issue(WsB, XsB, (kt + 2) * BK); else issue(WsA, XsA, (kt + 2) * BK);
-            MOE_WAIT_VMCNT(16);                  // stage kt+1 (issued one stage ago) has landed
+            warm((kt + 4) * BK);
+            MOE_WAIT_VMCNT(20);                  // stage kt+1 (issued one stage ago) has landed
         } else {
             MOE_WAIT_VMCNT(0);
         }
@@ -188,64 +221,52 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     __builtin_amdgcn_s_barrier();
 
     // ---- epilogue -----------------------------------------------------------------------------------
-    if (GATE_UP) {
-        // Raw g and u accumulators go through this wave's 32 KB of LDS (the stage buffers are free now) and
-        // come back paired, 8 consecutive features of one token per lane: silu(g)*u is formed there and
-        // stored as 16-byte pieces, 128 contiguous bytes per token row.
-        unsigned char *region = wave == 0 ? WsA : wave == 1 ? XsA : wave == 2 ? WsB : XsB;
-        constexpr int TROW = 32 * 4 + 16;                    // bytes per token row of a 32x32 float tile (padded)
-        constexpr int TILEB = 32 * TROW;
+    // The accumulators of one 32-token sub-tile go through this wave's 32 KB of LDS (the stage buffers are
+    // free now) and come back with 8 consecutive features of one token per lane, so that results leave as
+    // 16-byte pieces forming 128 (gate/up) or 256 (down) contiguous bytes per token row.
+    unsigned char *region = wave == 0 ? WsA : wave == 1 ? XsA : wave == 2 ? WsB : XsB;
+    constexpr int TROW = 32 * 4 + 16;                    // bytes per token row of a 32x32 float tile (padded)
+    constexpr int TILEB = 32 * TROW;
+    constexpr int LPR = GATE_UP ? 8 : 16;                // lanes per token row on the way out
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < 4; ++b) {
+        if (b >= nb) continue;
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
-                    *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int n = p * 8 + (lane >> 3);            // token inside the 32-token tile
-                const int c = lane & 7;                       // 8-feature piece of the wave's 64 features
-                const int at = c >> 2, fi = (c & 3) * 8;      // tile (0/1) and first feature inside it
-                const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
-                const unsigned char *up = gp + 2 * TILEB;
-                const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gp), g1 = *reinterpret_cast<const f32x4 *>(gp + 16);
-                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(up), u1 = *reinterpret_cast<const f32x4 *>(up + 16);
-                const int row = row0 + wt * 128 + b * 32 + n;
-                const int f = wrow0 + ww * 64 + c * 8;
-                if (row < row_end && f < NW) {
-                    u32x4 pk = {pack_bf16x2(silu_mul_f(g0[0], u0[0]), silu_mul_f(g0[1], u0[1])),
-                                pack_bf16x2(silu_mul_f(g0[2], u0[2]), silu_mul_f(g0[3], u0[3])),
-                                pack_bf16x2(silu_mul_f(g1[0], u1[0]), silu_mul_f(g1[1], u1[1])),
-                                pack_bf16x2(silu_mul_f(g1[2], u1[2]), silu_mul_f(g1[3], u1[3]))};
-                    *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
-                }
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
+                *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int p = 0; p < 32 * LPR / 64; ++p) {
+            const int n = p * (64 / LPR) + lane / LPR;    // token inside the 32-token sub-tile
+            const int c = lane % LPR;                     // 8-feature piece
+            const int at = c >> 2, fi = (c & 3) * 8;      // accumulator tile and first feature inside it
+            const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
+            const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gp), g1 = *reinterpret_cast<const f32x4 *>(gp + 16);
+            const int row = row0 + (2 * b + wt) * 32 + n;
+            u32x4 pk;
+            int f;
+            if (GATE_UP) {
+                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB), u1 = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB + 16);
+                pk = u32x4{pack_bf16x2(silu_mul_f(g0[0], u0[0]), silu_mul_f(g0[1], u0[1])),
+                           pack_bf16x2(silu_mul_f(g0[2], u0[2]), silu_mul_f(g0[3], u0[3])),
+                           pack_bf16x2(silu_mul_f(g1[0], u1[0]), silu_mul_f(g1[1], u1[1])),
+                           pack_bf16x2(silu_mul_f(g1[2], u1[2]), silu_mul_f(g1[3], u1[3]))};
+                f = wrow0 + ww * 64 + c * 8;
+            } else {
+                pk = u32x4{pack_bf16x2(g0[0], g0[1]), pack_bf16x2(g0[2], g0[3]), pack_bf16x2(g1[0], g1[1]), pack_bf16x2(g1[2], g1[3])};
+                f = wrow0 + ww * 128 + c * 8;
+            }
+            if (row < row_end && f < NW) *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
         }
-    } else {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int row = row0 + wt * 128 + b * 32 + (lane & 31);
-            if (row >= row_end) continue;
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int f = wrow0 + ww * 128 + a * 32 + 8 * rq + 4 * (lane >> 5);
-                    if (f >= NW) continue;
-                    u32x2 pk = {pack_bf16x2(acc[a][b][4 * rq], acc[a][b][4 * rq + 1]),
-                                pack_bf16x2(acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3])};
-                    *reinterpret_cast<u32x2 *>(outp + (size_t)row * NW + f) = pk;
-                }
-        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
