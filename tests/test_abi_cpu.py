@@ -1,0 +1,102 @@
+"""The C ABI without a GPU: the library loads, exports what include/moe_ffn.h declares, and rejects bad
+arguments on the host before any HIP call (so none of this needs a device)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_11373_amd import build as hip_build
+from paper_2511_11373_amd import moe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(moe.LIB_PATH):
+        hip_build.build()
+    return moe.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "moe_ffn.h")).read()
+    declared = set(re.findall(r"\b(moe_[a-z_]+)\s*\(", hdr))
+    assert declared == set(moe.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.moe_status_string(0) == b"ok" and lib.moe_status_string(2) == b"unsupported shape"
+    assert lib.moe_status_string(99) == b"unknown status"
+
+
+def _call_forward(lib, shape, ptrs, ws=0x1000, ws_bytes=1 << 40):
+    vp = ctypes.c_void_p
+    x, wr, bias, wg, wu, wd, out, idx, w = [vp(p) if p else None for p in ptrs]
+    return lib.moe_forward(ctypes.byref(shape), x, wr, bias, wg, wu, wd, out, idx, w, vp(ws) if ws else None,
+                           ws_bytes, None)
+
+
+GOOD = [0x1000, 0x2000, 0, 0x3000, 0x4000, 0x5000, 0x6000, 0, 0]      # fake, aligned, never dereferenced
+
+
+@pytest.mark.parametrize("fields,code", [
+    (dict(T=-1), 2), (dict(H=0), 2), (dict(E=0), 2), (dict(K=0), 2), (dict(K=9, E=8), 2), (dict(I=0), 2),
+    (dict(H=100), 2), (dict(I=12), 2), (dict(E=1025, K=1), 2), (dict(dtype=7), 3),
+    (dict(T=1 << 30, K=8, E=128), 2),
+])
+def test_bad_shapes_are_rejected_on_the_host(lib, fields, code):
+    base = dict(T=4, H=64, E=8, K=2, I=32, dtype=0, renormalize=1)
+    base.update(fields)
+    shape = moe.MoeShape(*[base[k] for k in ("T", "H", "E", "K", "I", "dtype", "renormalize")])
+    assert _call_forward(lib, shape, GOOD) == code
+    out = ctypes.c_size_t(123)
+    assert lib.moe_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)) == code and out.value == 123
+
+
+def test_null_alignment_and_workspace_errors(lib):
+    shape = moe.make_shape(4, 64, 8, 2, 32, moe.MOE_BF16)
+    for i in (0, 1, 3, 4, 5, 6):                      # every required pointer
+        p = list(GOOD)
+        p[i] = 0
+        assert _call_forward(lib, shape, p) == 1
+    p = list(GOOD)
+    p[0] = 0x1008
+    assert _call_forward(lib, shape, p) == 5
+    p = list(GOOD)
+    p[2] = 0x7004                                     # optional bias, misaligned
+    assert _call_forward(lib, shape, p) == 5
+    assert _call_forward(lib, shape, GOOD, ws=0) == 4
+    assert _call_forward(lib, shape, GOOD, ws=0x1004) == 5
+    need = moe.workspace_bytes(shape)
+    assert need % 256 == 0 and need > 0
+    assert _call_forward(lib, shape, GOOD, ws_bytes=need - 1) == 4
+    assert lib.moe_workspace_bytes(ctypes.byref(shape), None) == 1
+    assert lib.moe_workspace_bytes(None, None) == 1
+
+
+def test_every_entry_point_validates_and_accepts_an_empty_batch(lib):
+    vp = ctypes.c_void_p
+    bad = moe.make_shape(4, 64, 8, 9, 32, moe.MOE_BF16)
+    empty = moe.make_shape(0, 64, 8, 2, 32, moe.MOE_BF16)
+    a = [vp(0x1000 * (i + 1)) for i in range(8)]
+    big = 1 << 40
+    for shape, code in ((bad, 2), (empty, 0)):
+        s = ctypes.byref(shape)
+        assert lib.moe_route_topk(s, a[0], a[1], None, a[2], a[3], a[4], big, None) == code
+        assert lib.moe_permute(s, a[0], a[1], a[2], a[3], a[4], a[5], a[6], big, None) == code
+        assert lib.moe_grouped_swiglu(s, a[0], a[1], a[2], a[3], a[4], a[5], a[6], big, None) == code
+        assert lib.moe_combine(s, a[0], a[1], a[2], a[3], None) == code
+        assert _call_forward(lib, shape, GOOD) == code
+    s = ctypes.byref(empty)
+    assert lib.moe_permute(s, a[0], None, a[2], a[3], a[4], a[5], a[6], big, None) == 1    # x_perm without x
+    assert lib.moe_route_topk(s, None, a[1], None, a[2], a[3], a[4], big, None) == 1
+    ms = (ctypes.c_float * moe.NUM_STAGES)()
+    assert lib.moe_forward_stage_times(s, a[0], a[1], None, a[2], a[3], a[4], a[5], a[6], big, None, ms) == 0
+    assert lib.moe_forward_stage_times(s, a[0], a[1], None, a[2], a[3], a[4], a[5], a[6], big, None, None) == 1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(moe, "_lib", None)
+    monkeypatch.setattr(moe, "LIB_PATH", str(tmp_path / "libmoe_ffn.so"))
+    with pytest.raises(FileNotFoundError):
+        moe.load_library()
