@@ -67,16 +67,19 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 //   GATE_UP: weight tile = BW rows of Wg and the same BW rows of Wu, output act (bf16).
 //   else   : weight tile = BW rows of Wd, output y in the storage type SO.
 // SX/SW: storage type of the token rows / of the weights (bf16 bits or float, rounded on load).
-template <typename SX, typename SW, typename SO, bool GATE_UP, int WW, int WT, int MW, int MT>
+// Small batches are bound by the weight stream, so what matters is bytes in flight: the k tiles of
+// the next TWO steps sit in registers (global loads issued, not yet waited for) while the current one
+// is multiplied out of LDS.
+template <typename SX, typename SW, typename SO, bool GATE_UP, int WW, int WT, int MW, int MT, int BK>
 __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
     const SX *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
     const int32_t *__restrict__ off, const int32_t *__restrict__ tile_map, int max_tiles,
     const SW *__restrict__ w0, const SW *__restrict__ w1, SO *__restrict__ outp,
     int KD /* reduction length */, int NW /* weight rows per expert */) {
     constexpr int NT = WW * WT * 64;
-    constexpr int BW = WW * MW * 32, BT = WT * MT * 32, BK = 64, LDK = BK + 8;
+    constexpr int BW = WW * MW * 32, BT = WT * MT * 32, LDK = BK + 8, CPR = BK / 8;   // 16-byte chunks per row
     constexpr int NMAT = GATE_UP ? 2 : 1;
-    constexpr int WCH = NMAT * BW * (BK / 8), XCH = BT * (BK / 8);      // 16-byte chunks per k tile
+    constexpr int WCH = NMAT * BW * CPR, XCH = BT * CPR;                              // chunks per k tile
     constexpr int WPT = (WCH + NT - 1) / NT, XPT = (XCH + NT - 1) / NT;
     __shared__ __attribute__((aligned(16))) bf16_t Ws[NMAT * BW * LDK];
     __shared__ __attribute__((aligned(16))) bf16_t Xs[BT * LDK];
@@ -89,12 +92,12 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ww = wave % WW, wt = wave / WW;
 
-    // staging assignments: chunk c -> (row c/8, k piece c%8)
+    // staging assignments: chunk c -> (row c/CPR, k piece c%CPR)
     const SW *wsrc[WPT]; bool wok[WPT]; int wdst[WPT];
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
         const int c = tid + i * NT;
-        const int mat = c / (BW * 8), r = (c / 8) % BW, kc = c % 8;
+        const int mat = c / (BW * CPR), r = (c / CPR) % BW, kc = c % CPR;
         const int wr = wrow0 + r;
         wok[i] = c < WCH && wr < NW;
         const SW *base = (GATE_UP && mat == 1) ? w1 : w0;
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         const int c = tid + i * NT;
-        const int r = c / 8, kc = c % 8;
+        const int r = c / CPR, kc = c % CPR;
         const int row = row0 + r;
         xok[i] = c < XCH && row < row_end;
         int src = xok[i] ? row : row0;
@@ -124,25 +127,26 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[m][a][b][r] = 0.f;
 
-    u32x4 wreg[WPT], xreg[XPT];
-    auto fetch = [&](int k0) {
+    u32x4 wreg[2][WPT], xreg[2][XPT];
+    auto fetch = [&](int k0, int set) {
 #pragma unroll
-        for (int i = 0; i < WPT; ++i) wreg[i] = load8_bf16(wsrc[i] + k0, wok[i] && (k0 + (tid + i * NT) % 8 * 8) < KD);
+        for (int i = 0; i < WPT; ++i)
+            wreg[set][i] = load8_bf16(wsrc[i] + k0, wok[i] && (k0 + (tid + i * NT) % CPR * 8) < KD);
 #pragma unroll
-        for (int i = 0; i < XPT; ++i) xreg[i] = load8_bf16(xsrc[i] + k0, xok[i] && (k0 + (tid + i * NT) % 8 * 8) < KD);
+        for (int i = 0; i < XPT; ++i)
+            xreg[set][i] = load8_bf16(xsrc[i] + k0, xok[i] && (k0 + (tid + i * NT) % CPR * 8) < KD);
     };
-    fetch(0);
     const int arow = lane & 31, akq = (lane >> 5) * 8;
-    for (int k0 = 0; k0 < KD; k0 += BK) {
+    auto step = [&](int k0, int set) {      // k tile at k0 is in registers `set`
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < WPT; ++i)
-            if (tid + i * NT < WCH) *reinterpret_cast<u32x4 *>(&Ws[wdst[i]]) = wreg[i];
+            if (tid + i * NT < WCH) *reinterpret_cast<u32x4 *>(&Ws[wdst[i]]) = wreg[set][i];
 #pragma unroll
         for (int i = 0; i < XPT; ++i)
-            if (tid + i * NT < XCH) *reinterpret_cast<u32x4 *>(&Xs[xdst[i]]) = xreg[i];
+            if (tid + i * NT < XCH) *reinterpret_cast<u32x4 *>(&Xs[xdst[i]]) = xreg[set][i];
         __syncthreads();
-        if (k0 + BK < KD) fetch(k0 + BK);
+        if (k0 + 2 * BK < KD) fetch(k0 + 2 * BK, set);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 bop[MT];
@@ -160,6 +164,12 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
                         acc[m][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[b], acc[m][a][b], 0, 0, 0);
                 }
         }
+    };
+    fetch(0, 0);
+    if (BK < KD) fetch(BK, 1);
+    for (int k0 = 0; k0 < KD; k0 += 2 * BK) {
+        step(k0, 0);
+        if (k0 + BK < KD) step(k0 + BK, 1);
     }
 
     // epilogue: lane holds token (l%32), features 8*(r/4) + 4*(l/32) + 0..3
@@ -192,11 +202,25 @@ hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows,
                                      bf16_t *act, const int32_t *tile_map, int max_tiles, bf16_t *y_perm,
                                      hipStream_t st, Probe *probe);
 
+// decode-sized bf16 variant (grouped_swiglu_stream.hip); needs no row-tile list
+bool stream_gemm_applicable(const moe_shape_t &s);
+hipError_t launch_grouped_swiglu_stream(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
+                                        const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
+                                        bf16_t *act, bf16_t *y_perm, hipStream_t st, Probe *probe);
+
 constexpr int kWW = 2, kWT = 2, kMW = 1, kMT = 1;      // wave grid and MFMA tiles per wave of the tiled kernel
-int gemm_tile_rows(const moe_shape_t &s) { return big_gemm_applicable(s) ? big_tile_rows() : kWT * kMT * 32; }
+#ifndef MOE_SMALL_BK
+#define MOE_SMALL_BK 64
+#endif
+constexpr int kBK = MOE_SMALL_BK;
+int gemm_tile_rows(const moe_shape_t &s) {
+    if (stream_gemm_applicable(s)) return 0;      // no tile list
+    return big_gemm_applicable(s) ? big_tile_rows() : kWT * kMT * 32;
+}
 int gemm_max_tiles(const moe_shape_t &s) {
     const int n = s.T * s.K;
-    return n / gemm_tile_rows(s) + (s.E < n ? s.E : n);
+    const int rows = gemm_tile_rows(s);
+    return rows ? n / rows + (s.E < n ? s.E : n) : 0;
 }
 
 template <typename S>
@@ -205,6 +229,12 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
                                int32_t *tile_map, S *y_perm, hipStream_t st, Probe *probe, bool tile_map_ready) {
     constexpr int WW = kWW, WT = kWT, MW = kMW, MT = kMT;
     constexpr int BW = WW * MW * 32, BT = WT * MT * 32;
+    if constexpr (sizeof(S) == 2) {
+        if (stream_gemm_applicable(s)) {
+            probe_mark(probe);
+            return launch_grouped_swiglu_stream(s, x_rows, row_map, off, wg, wu, wd, act, y_perm, st, probe);
+        }
+    }
     const int max_tiles = gemm_max_tiles(s);
     hipError_t err = hipSuccess;
     if (!tile_map_ready) {
@@ -217,12 +247,12 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
         if (big_gemm_applicable(s))
             return launch_grouped_swiglu_big(s, x_rows, row_map, off, wg, wu, wd, act, tile_map, max_tiles, y_perm, st, probe);
     }
-    hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT>), dim3(max_tiles, (s.I + BW - 1) / BW),
+    hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT, kBK>), dim3(max_tiles, (s.I + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, x_rows, row_map, s.K, off, tile_map, max_tiles, wg, wu, act, s.H, s.I);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     probe_mark(probe);
-    hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MW, MT>), dim3(max_tiles, (s.H + BW - 1) / BW),
+    hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MW, MT, kBK>), dim3(max_tiles, (s.H + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, (const bf16_t *)act, (const int32_t *)nullptr, 1, off, tile_map,
                        max_tiles, wd, wd, y_perm, s.I, s.H);
     return hipGetLastError();
