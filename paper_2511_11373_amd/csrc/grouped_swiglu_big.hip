@@ -125,14 +125,12 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    auto issue = [&](unsigned char *Ws, unsigned char *Xs, int k0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const bf16_t *wp = GATE_UP ? (i < 4 ? wbase0 + i * wstride : wbase1 + (i - 4) * wstride) : wbase0 + i * wstride;
-            __builtin_amdgcn_global_load_lds((gbl_void *)(wp + k0), (lds_void *)(Ws + (i * 4 + wave) * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gbl_void *)(xbase + (size_t)xrow[i] * KD + k0),
-                                             (lds_void *)(Xs + (i * 4 + wave) * 1024), 16, 0, 0);
-        }
+    // one weight piece and one token piece per thread: pair i fills LDS rows (i*4 + wave)*8 .. +8 of both operands
+    auto issue_pair = [&](unsigned char *Ws, unsigned char *Xs, int k0, int i) {
+        const bf16_t *wp = GATE_UP ? (i < 4 ? wbase0 + i * wstride : wbase1 + (i - 4) * wstride) : wbase0 + i * wstride;
+        __builtin_amdgcn_global_load_lds((gbl_void *)(wp + k0), (lds_void *)(Ws + (i * 4 + wave) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_void *)(xbase + (size_t)xrow[i] * KD + k0),
+                                         (lds_void *)(Xs + (i * 4 + wave) * 1024), 16, 0, 0);
     };
     const int k_last = KD - BK;
     auto warm = [&](int k0) {        // two 4-byte loads per thread whose only purpose is to pull lines into L2
@@ -170,54 +168,59 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
             }
     };
+    // the same with one load pair slipped in after every four MFMAs: the address unit works through the
+    // loads in the shadow of the matrix pipe instead of stalling all four waves at once
+    auto mfma16_load = [&](int set, bool load, unsigned char *Ws, unsigned char *Xs, int k0, int i0) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (b < nb) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+            }
+            if (load) issue_pair(Ws, Xs, k0, i0 + b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
     // ---- main loop ------------------------------------------------------------------------------------
-    // Two LDS stages.  While stage kt is multiplied, the loads of stage kt+1 (issued a whole stage earlier)
-    // land in the other buffer; operand registers are double-buffered per 16-wide k step.  Lines of stage
-    // kt+4 are pulled into L2 two stages before their real load is issued.
-    // Loads retire in order; between the loads of stage kt+1 and the wait for them lie 2 warm-up loads, the 16
-    // loads of stage kt+2 and 2 more warm-up loads: vmcnt(20).
+    // Two LDS stages, one block barrier per stage.  While stage kt is multiplied out of one buffer, the 16
+    // loads of stage kt+1 are issued into the other, interleaved with the MFMAs of the first two k steps; the
+    // last two k steps (32 MFMAs) cover their latency, helped by warm-up loads that pull the lines of stage
+    // kt+3 into L2.  Operand registers are double-buffered per 16-wide k step.
+    // Loads retire in order: at the end of a stage only the 2 warm-up loads may still be in flight (vmcnt(2)).
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
-    issue(WsA, XsA, 0);
-    if (nk > 1) {
-        issue(WsB, XsB, BK);
-        warm(2 * BK);
-        warm(3 * BK);
-        MOE_WAIT_VMCNT(20);
-    } else {
-        MOE_WAIT_VMCNT(0);
-    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) issue_pair(WsA, XsA, 0, i);
+    warm(BK);
+    warm(2 * BK);
+    MOE_WAIT_VMCNT(4);
     __builtin_amdgcn_s_barrier();
     read_ops(wsA, xsA, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
-        const bool odd = kt & 1;
+        const bool odd = kt & 1, more = kt + 1 < nk;
         const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
         const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
+        unsigned char *Wn = odd ? WsA : WsB, *Xn = odd ? XsA : XsB;
+        const int k_next = (kt + 1) * BK;
         read_ops(wcur, xcur, 1, 1);
         wait_lds_reads<8>(aop[0], bop[0]);
-        mfma16(0);
+        mfma16_load(0, more, Wn, Xn, k_next, 0);
         read_ops(wcur, xcur, 2, 0);
         wait_lds_reads<8>(aop[1], bop[1]);
-        mfma16(1);
+        mfma16_load(1, more, Wn, Xn, k_next, 4);
         read_ops(wcur, xcur, 3, 1);
         wait_lds_reads<8>(aop[0], bop[0]);
         mfma16(0);
-        wait_lds_reads<0>(aop[1], bop[1]);       // every read of the current stage has landed
-        __builtin_amdgcn_s_barrier();            // ... in every wave: the buffer may be refilled
-        if (kt + 2 < nk) {
-            if (odd) issue(WsB, XsB, (kt + 2) * BK); else issue(WsA, XsA, (kt + 2) * BK);
-            warm((kt + 4) * BK);
-            MOE_WAIT_VMCNT(20);                  // stage kt+1 (issued one stage ago) has landed
-        } else {
-            MOE_WAIT_VMCNT(0);
-        }
-        if (kt + 1 < nk) {
-            __builtin_amdgcn_s_barrier();        // ... in every wave
-            read_ops(wnxt, xnxt, 0, 0);
-        }
+        warm((kt + 3) * BK);
+        wait_lds_reads<0>(aop[1], bop[1]);       // every read of the current stage has landed ...
+        MOE_WAIT_VMCNT(2);                       // ... and so has every load of the next one
+        __builtin_amdgcn_s_barrier();            // ... in every wave
+        if (more) read_ops(wnxt, xnxt, 0, 0);
         mfma16(1);
     }
+    MOE_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
 
     // ---- epilogue -----------------------------------------------------------------------------------

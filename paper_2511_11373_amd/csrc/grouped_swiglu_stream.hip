@@ -14,7 +14,14 @@
 namespace moe {
 
 namespace stream {
-constexpr int NI = 4;                 // items per block (gate/up) or per wave (down)
+#ifndef MOE_NIG
+#define MOE_NIG 2
+#endif
+#ifndef MOE_NID
+#define MOE_NID 1
+#endif
+constexpr int NIG = MOE_NIG;           // items per block, gate/up
+constexpr int NID = MOE_NID;           // items per wave, down
 constexpr int GROW = 1024 + 16;       // LDS bytes per staged gate/up row piece (1 KB + pad: conflict-free reads)
 constexpr int DHALF = 768 + 16;       // LDS bytes per staged half row of Wd (I = 768 only)
 }  // namespace stream
@@ -23,11 +30,11 @@ __device__ __forceinline__ float silu_mul_s(float g, float u) { return g / (1.0f
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ---- gate/up ------------------------------------------------------------------------------------------
-// Block (ib, e): NI items of 8 features of expert e.  An item is 8 rows of Wg and the same 8 rows of Wu;
+// Block (ib, e): NIG items of 8 features of expert e.  An item is 8 rows of Wg and the same 8 rows of Wu;
 // wave w multiplies the k range [512w, 512w+512) of all 16 rows, the four partial 16x16 results meet in
 // LDS and wave (item % 4) applies silu(g)*u.  MFMA row 4q+j is gate feature 2q+j (j < 2) or up feature
 // 2q+j-2, so a lane ends up with g and u of the same two features of one token.
-// Requires H == 2048 (4 waves x 512), I % (8*NI) == 0, bf16 storage.
+// Requires H == 2048 (4 waves x 512), I % (8*NIG) == 0, bf16 storage.  (NIG = 2, NID = 1 measured best.)
 __global__ __launch_bounds__(256, 2) void stream_gate_up_kernel(
     const bf16_t *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
     const int32_t *__restrict__ off, const bf16_t *__restrict__ wg, const bf16_t *__restrict__ wu,
@@ -41,7 +48,7 @@ __global__ __launch_bounds__(256, 2) void stream_gate_up_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, q = lane >> 4;
     const int kbase = wave * 512;
-    const int feat0 = blockIdx.x * (8 * NI);
+    const int feat0 = blockIdx.x * (8 * NIG);
 
     // this lane's piece of each of the 16 rows of an item: bytes [16*lane, +16) of the wave's 1 KB of the row
     const size_t wrow_off = ((size_t)e * I + feat0) * H + kbase + lane * 8;
@@ -84,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void stream_gate_up_kernel(
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __builtin_amdgcn_sched_barrier(0);
-            if (item + 1 < NI) fetch(item + 1);           // in flight while this item is multiplied
+            if (item + 1 < NIG) fetch(item + 1);           // in flight while this item is multiplied
             __builtin_amdgcn_sched_barrier(0);
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -110,15 +117,15 @@ __global__ __launch_bounds__(256, 2) void stream_gate_up_kernel(
         };
         fetch(0);
 #pragma unroll 1
-        for (int item = 0; item < NI; ++item) work(item);   // not unrolled: keeps one item's loads in registers
+        for (int item = 0; item < NIG; ++item) work(item);   // not unrolled: keeps one item's loads in registers
         __syncthreads();       // partial[] and stage[] are reused by the next token group
     }
 }
 
 // ---- down -----------------------------------------------------------------------------------------------
-// Wave (jb, e): NI items of 16 output features, each handled as two units of 16 rows x 384 k (768 bytes per
+// Wave (jb, e): NID items of 16 output features, each handled as two units of 16 rows x 384 k (768 bytes per
 // row, 12 KB per unit, twelve coalesced 16-byte loads per lane).  Waves are independent: no k split across
-// waves, no block barrier.  Requires I == 768, H % (64*NI) == 0, bf16 weights.
+// waves, no block barrier.  Requires I == 768, H % (64*NID) == 0, bf16 weights.
 template <typename SO>
 __global__ __launch_bounds__(256, 2) void stream_down_kernel(
     const bf16_t *__restrict__ act, const int32_t *__restrict__ off, const bf16_t *__restrict__ wd,
@@ -130,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void stream_down_kernel(
     if (r_begin == r_end) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, q = lane >> 4;
-    const int j0 = (blockIdx.x * 4 + wave) * (16 * NI);
+    const int j0 = (blockIdx.x * 4 + wave) * (16 * NID);
     unsigned char *mine = stage[wave];
     // piece p = c*64 + lane of a unit -> row p/48, 16-byte column p%48; three loads cover four rows
     int goff[3], soff[3];
@@ -165,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void stream_down_kernel(
         };
         fetch(0);
 #pragma unroll 1
-        for (int item = 0; item < NI; ++item) {              // not unrolled: keeps one unit's loads in registers
+        for (int item = 0; item < NID; ++item) {              // not unrolled: keeps one unit's loads in registers
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -176,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void stream_down_kernel(
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 __builtin_amdgcn_sched_barrier(0);
-                if (unit + 1 < 2 * NI) fetch(unit + 1);      // in flight while this unit is multiplied
+                if (unit + 1 < 2 * NID) fetch(unit + 1);      // in flight while this unit is multiplied
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int s = 0; s < 12; ++s) {
@@ -204,7 +211,7 @@ __global__ __launch_bounds__(256, 2) void stream_down_kernel(
 
 bool stream_gemm_applicable(const moe_shape_t &s) {
     using namespace stream;
-    return s.dtype == MOE_BF16 && s.H == 2048 && s.I == 768 && s.I % (8 * NI) == 0 && s.H % (64 * NI) == 0 &&
+    return s.dtype == MOE_BF16 && s.H == 2048 && s.I == 768 && s.I % (8 * NIG) == 0 && s.H % (64 * NID) == 0 &&
            (long)s.T * s.K <= 8L * s.E;
 }
 
@@ -212,12 +219,12 @@ hipError_t launch_grouped_swiglu_stream(const moe_shape_t &s, const bf16_t *x_ro
                                         const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
                                         bf16_t *act, bf16_t *y_perm, hipStream_t st, Probe *probe) {
     using namespace stream;
-    hipLaunchKernelGGL(stream_gate_up_kernel, dim3(s.I / (8 * NI), s.E), dim3(256), 0, st, x_rows, row_map, s.K, off, wg,
+    hipLaunchKernelGGL(stream_gate_up_kernel, dim3(s.I / (8 * NIG), s.E), dim3(256), 0, st, x_rows, row_map, s.K, off, wg,
                        wu, act, s.H, s.I);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     probe_mark(probe);
-    hipLaunchKernelGGL(stream_down_kernel<bf16_t>, dim3(s.H / (64 * NI), s.E), dim3(256), 0, st, (const bf16_t *)act, off,
+    hipLaunchKernelGGL(stream_down_kernel<bf16_t>, dim3(s.H / (64 * NID), s.E), dim3(256), 0, st, (const bf16_t *)act, off,
                        wd, y_perm, s.H, s.I);
     return hipGetLastError();
 }

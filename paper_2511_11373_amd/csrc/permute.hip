@@ -133,10 +133,11 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_sums /* [17
     return before + inc - v;
 }
 
-// n <= 16 * kPermChunk assignments.  Wave w owns chunk w.  Same three steps as the large path with
+// n <= 16 * kPermChunk assignments.  Wave w owns chunk w of `chunk` assignments (a multiple of 64 chosen
+// by the launcher so that all 16 waves have work).  Same three steps as the large path with
 // the histograms kept in LDS.  With tile_rows > 0 it also writes the list of (expert, first row) row
 // tiles that the grouped GEMM consumes: tile_map[2*i], tile_map[2*i+1], count at tile_map[2*max_tiles].
-__global__ __launch_bounds__(1024) void permute_small_kernel(const int32_t *__restrict__ idx, int n, int E, int ebits,
+__global__ __launch_bounds__(1024) void permute_small_kernel(const int32_t *__restrict__ idx, int n, int chunk, int E, int ebits,
                                                              int32_t *__restrict__ expert_offsets,
                                                              int32_t *__restrict__ row_to_assign,
                                                              int32_t *__restrict__ assign_to_row, int tile_rows,
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(1024) void permute_small_kernel(const int32_t *__re
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int i = threadIdx.x; i < 16 * E; i += 1024) lds[i] = 0;
     __syncthreads();
-    const int a0 = wave * kPermChunk, a1 = min(a0 + kPermChunk, n);
+    const int a0 = min(wave * chunk, n), a1 = min(a0 + chunk, n);
     int *mine = lds + (size_t)wave * E;
     for (int a = a0 + lane; a < a1; a += 64) atomicAdd(&mine[min(max(idx[a], 0), E - 1)], 1);
     __syncthreads();
@@ -220,8 +221,9 @@ hipError_t launch_permute(const moe_shape_t &s, const int32_t *topk_idx, int32_t
     int ebits = 0;
     while ((1 << ebits) < s.E) ++ebits;
     if (permute_is_small(s)) {
+        const int chunk = ((n + 16 * 64 - 1) / (16 * 64)) * 64;
         hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(1024), (size_t)16 * s.E * sizeof(int), st, topk_idx, n,
-                           s.E, ebits, expert_offsets, row_to_assign, assign_to_row, tile_rows, max_tiles, tile_map);
+                           chunk, s.E, ebits, expert_offsets, row_to_assign, assign_to_row, tile_rows, max_tiles, tile_map);
         return hipGetLastError();
     }
     const int nchunks = (n + kPermChunk - 1) / kPermChunk;
