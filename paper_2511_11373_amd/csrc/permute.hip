@@ -27,50 +27,62 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__rest
 }
 
 // Step 2: one block.  Turns the histograms into the first output row of every (chunk, expert) and
-// writes expert_offsets.  Thread (p, e): p-th slice of the chunks, expert e (+ a loop when E > blockDim/P).
+// writes expert_offsets.  Thread (p, e) owns the p-th slice of the chunk range of expert e; P slices per
+// expert with P * E <= 1024, so one pass covers all experts.
 __global__ __launch_bounds__(1024) void permute_scan_kernel(int32_t *__restrict__ chunk_base, int nchunks, int E,
                                                             int32_t *__restrict__ expert_offsets) {
-    __shared__ int part[1024];       // [P][Epad] slice sums, Epad*P <= 1024
+    __shared__ int part[1024];       // [P][G] slice sums
     __shared__ int etotal[kMaxExperts + 1];
-    // P slices of the chunk range per expert, experts processed in groups of G = 1024 / P.
     int P = 1;
     while (P < 16 && P * 2 * E <= 1024 && P * 2 <= nchunks) P *= 2;
-    const int G = 1024 / P;
+    const int G = 1024 / P;          // >= E
     const int cps = (nchunks + P - 1) / P;
-    for (int eg = 0; eg < E; eg += G) {
-        const int p = threadIdx.x / G, e = eg + threadIdx.x % G;
-        const int cb = p * cps, ce = min(cb + cps, nchunks);
-        int s = 0;
-        if (p < P && e < E)
-            for (int c = cb; c < ce; ++c) s += chunk_base[(size_t)c * E + e];
-        part[threadIdx.x] = s;
-        __syncthreads();
-        if (p < P && e < E) {
-            int before = 0, tot = 0;
-            for (int pp = 0; pp < P; ++pp) {
-                const int v = part[pp * G + threadIdx.x % G];
-                if (pp < p) before += v;
-                tot += v;
-            }
-            if (p == 0) etotal[e] = tot;
-            int run = before;       // rows of expert e in chunks before slice p
-            for (int c = cb; c < ce; ++c) {
-                const int v = chunk_base[(size_t)c * E + e];
-                chunk_base[(size_t)c * E + e] = run;
-                run += v;
-            }
+    const int p = threadIdx.x / G, e = threadIdx.x % G;
+    const int cb = p * cps, ce = min(cb + cps, nchunks);
+    const bool mine = e < E;
+    // the walks over this thread's chunks fetch 8 counts at a time so that the loads overlap
+    int s = 0;
+    if (mine)
+        for (int c = cb; c < ce; c += 8) {
+            int v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = c + j < ce ? chunk_base[(size_t)(c + j) * E + e] : 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[j];
         }
-        __syncthreads();
+    part[threadIdx.x] = s;
+    __syncthreads();
+    int before = 0;                  // rows of expert e in the slices before p
+    if (mine) {
+        int tot = 0;
+        for (int pp = 0; pp < P; ++pp) {
+            const int v = part[pp * G + e];
+            if (pp < p) before += v;
+            tot += v;
+        }
+        if (p == 0) etotal[e] = tot;
     }
-    // exclusive scan over experts (serial; E <= 1024)
-    if (threadIdx.x == 0) {
+    __syncthreads();
+    if (threadIdx.x == 0) {          // exclusive scan over experts (serial; E <= 1024)
         int run = 0;
-        for (int e = 0; e < E; ++e) { const int v = etotal[e]; etotal[e] = run; run += v; }
+        for (int i = 0; i < E; ++i) { const int v = etotal[i]; etotal[i] = run; run += v; }
         etotal[E] = run;
     }
     __syncthreads();
-    for (int e = threadIdx.x; e <= E; e += 1024) expert_offsets[e] = etotal[e];
-    for (size_t i = threadIdx.x; i < (size_t)nchunks * E; i += 1024) chunk_base[i] += etotal[i % E];
+    for (int i = threadIdx.x; i <= E; i += 1024) expert_offsets[i] = etotal[i];
+    if (mine) {
+        int run = etotal[e] + before;
+        for (int c = cb; c < ce; c += 8) {
+            int v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = c + j < ce ? chunk_base[(size_t)(c + j) * E + e] : 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (c + j < ce) chunk_base[(size_t)(c + j) * E + e] = run;
+                run += v[j];
+            }
+        }
+    }
 }
 
 // Step 3: one wave per chunk.  Walks its assignments 64 at a time in order; lanes holding the same

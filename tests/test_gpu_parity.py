@@ -21,6 +21,8 @@ SMALL = [
     wl.small_config(200, 128, 1, 1, 64, dtype=wl.BF16, seed=4, sigma_w=0.1),       # a single expert
     wl.small_config(700, 256, 70, 4, 96, dtype=wl.BF16, seed=5, sigma_w=0.05),     # E not a multiple of 64, 2800 rows
     wl.small_config(96, 512, 300, 8, 64, dtype=wl.BF16, seed=6, sigma_w=0.05),     # many experts, most nearly empty
+    wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=10, sigma_w=0.05),   # large batch: matrix-core router, big GEMM off
+    wl.small_config(2100, 256, 8, 2, 128, dtype=wl.BF16, seed=11, sigma_w=0.05),   # 525 rows per expert: big GEMM with ragged tiles
     wl.small_config(260, 256, 16, 2, 128, dtype=wl.BF16, seed=7, renormalize=False, sigma_w=0.05),
 ]
 
@@ -110,6 +112,32 @@ def test_tie_break_and_zero_input(lib, oracle_lib):
     assert np.array_equal(host(idx), o_idx)
     out = moe.moe_forward(shp, torch.zeros_like(g["x"]), g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], ws)
     assert torch.count_nonzero(out).item() == 0
+
+
+def test_near_ties_go_through_the_exact_recheck(lib, oracle_lib):
+    """Router rows that differ from each other by one bf16 ulp in a few places, and exact duplicates: the
+    logits of such experts differ by far less than float accumulation error, so only an exact re-evaluation
+    can order them.  Shapes on both the matrix-core fast path (T >= 1024, H % 256 == 0, E <= 128) and the fp64 path."""
+    for (T, H, E, K, seed) in ((1100, 512, 96, 8, 21), (1025, 2048, 128, 8, 22), (300, 512, 96, 8, 24), (64, 384, 40, 6, 23)):
+        cfg = wl.small_config(T, H, E, K, 64, dtype=wl.BF16, seed=seed, sigma_w=0.02)
+        d = wl.make_inputs(cfg)
+        wr = d["w_router"].copy()
+        rng = np.random.default_rng(seed)
+        for e in range(1, E):
+            if e % 3 == 0:
+                continue                                   # keep a third of the rows independent
+            wr[e] = wr[e - 1]                              # a chain of near-copies
+            if e % 3 == 1:
+                cols = rng.integers(0, H, 3)
+                wr[e, cols] = wr[e, cols] ^ np.uint16(1)   # flip the last mantissa bit: one ulp
+        bias = (rng.standard_normal(E) * 1e-4).astype(np.float32) if seed == 22 else None
+        shp = moe.make_shape(T, H, E, K, 64, moe.MOE_BF16)
+        ws = moe.alloc_workspace(shp)
+        idx, w = moe.moe_route_topk(shp, to_dev(d["x"], wl.BF16), to_dev(wr, wl.BF16),
+                                    None if bias is None else torch.from_numpy(bias).cuda(), ws)
+        o_idx, o_w = oracle_lib.route_topk(d["x_f32"], wl.bf16_bits_to_f32(wr), K, bias)
+        assert np.array_equal(host(idx), o_idx), (T, H, E)
+        check_weights(host(w), o_w)
 
 
 def test_empty_batch_and_bad_arguments(lib):
