@@ -154,9 +154,10 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
  *   stage_ms  host float[MOE_NUM_STAGES] out: elapsed milliseconds of
  *             [0] router logits  [1] top-K + weights  [2] permutation (3 kernels)
  *             [3] row-tile list  [4] gate/up GEMM + SiLU*mul  [5] down GEMM  [6] combine
+ *             [7] an empty interval (two events back to back): what the measurement itself adds to a stage
  * Same arguments, results and errors as moe_forward otherwise.
  */
-#define MOE_NUM_STAGES 7
+#define MOE_NUM_STAGES 8
 moe_status_t moe_forward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router,
                                      const float *router_bias, const void *w_gate, const void *w_up,
                                      const void *w_down, void *out, void *ws, size_t ws_bytes,

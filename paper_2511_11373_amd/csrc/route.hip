@@ -107,14 +107,13 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
 // rounded once to float.
 __device__ __forceinline__ float final_logit(const double *__restrict__ part, int ksplit, size_t split_stride,
                                              size_t pos, const float *__restrict__ bias, int e) {
+    // all partials are fetched before the first add so that the loads overlap (ksplit <= kMaxLogitSplit)
+    double v[kMaxLogitSplit];
+#pragma unroll
+    for (int z = 0; z < kMaxLogitSplit; ++z) v[z] = z < ksplit ? part[pos + (size_t)z * split_stride] : 0.0;
     double s = 0.0;
-    int z = 0;
-    for (; z + 4 <= ksplit; z += 4) {
-        const double a = part[pos + (size_t)z * split_stride], b = part[pos + (size_t)(z + 1) * split_stride];
-        const double c = part[pos + (size_t)(z + 2) * split_stride], d = part[pos + (size_t)(z + 3) * split_stride];
-        s = (((s + a) + b) + c) + d;
-    }
-    for (; z < ksplit; ++z) s += part[pos + (size_t)z * split_stride];
+#pragma unroll
+    for (int z = 0; z < kMaxLogitSplit; ++z) s += v[z];      // adding 0.0 for the unused splits changes nothing
     if (bias) s += (double)bias[e];
     return (float)s;
 }

@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libmoe_ffn.so")
 MOE_BF16, MOE_F32 = 0, 1
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_topk", "moe_permute",
            "moe_grouped_swiglu", "moe_combine", "moe_forward", "moe_forward_stage_times")
-NUM_STAGES = 7
-STAGE_NAMES = ("router_logits", "topk", "permute", "tile_list", "gate_up_gemm", "down_gemm", "combine")
+NUM_STAGES = 8
+STAGE_NAMES = ("router_logits", "topk", "permute", "tile_list", "gate_up_gemm", "down_gemm", "combine", "empty_interval")
 
 
 class MoeShape(ctypes.Structure):
