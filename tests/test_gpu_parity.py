@@ -21,6 +21,8 @@ SMALL = [
     wl.small_config(200, 128, 1, 1, 64, dtype=wl.BF16, seed=4, sigma_w=0.1),       # a single expert
     wl.small_config(700, 256, 70, 4, 96, dtype=wl.BF16, seed=5, sigma_w=0.05),     # E not a multiple of 64, 2800 rows
     wl.small_config(96, 512, 300, 8, 64, dtype=wl.BF16, seed=6, sigma_w=0.05),     # many experts, most nearly empty
+    wl.small_config(40, 64, 1024, 16, 16, dtype=wl.BF16, seed=12, sigma_w=0.1),      # the largest expert count the library takes
+    wl.small_config(600, 64, 1024, 16, 16, dtype=wl.F32, seed=13, sigma_w=0.1),      # ... with the multi-block permutation (9600 rows)
     wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=10, sigma_w=0.05),   # large batch: matrix-core router, big GEMM off
     wl.small_config(2100, 256, 8, 2, 128, dtype=wl.BF16, seed=11, sigma_w=0.05),   # 525 rows per expert: big GEMM with ragged tiles
     wl.small_config(260, 256, 16, 2, 128, dtype=wl.BF16, seed=7, renormalize=False, sigma_w=0.05),
