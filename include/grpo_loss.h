@@ -49,7 +49,7 @@ moe_status_t grpo_token_logprob(const grpo_shape_t *shape, const void *logits, c
 
 /* Eq. 1-3 from token log-probabilities.
  *   logp, logp_old, logp_ref [N] float; rewards [G] float; resp_offsets [G+1] int32 (non-decreasing, as above)
- *   advantage [G] float out; token_term [N] float out or NULL; resp_mean [G] float out; objective [1] float out */
+ *   advantage [G] float out; token_term [N] float out; resp_mean [G] float out; objective [1] float out */
 moe_status_t grpo_objective(const grpo_shape_t *shape, const float *logp, const float *logp_old,
                             const float *logp_ref, const float *rewards, const int32_t *resp_offsets,
                             float *advantage, float *token_term, float *resp_mean, float *objective,

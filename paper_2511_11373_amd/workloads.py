@@ -50,12 +50,19 @@ CONFIGS: Dict[str, MoEConfig] = {
 }
 
 
-def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
-    """Round fp32 values to the nearest bf16 (ties to even); returns uint16 bits."""
+def f32_to_bf16_bits_numpy(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); returns uint16 bits.  Reference bit arithmetic."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
     lsb = (u >> np.uint32(16)) & np.uint32(1)
     r = u + np.uint32(0x7FFF) + lsb
     return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Same rounding through torch's conversion (several times faster on large tensors; the two are tested equal)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.uint16).numpy()
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -177,3 +184,64 @@ def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True) -> D
 def small_config(T: int, H: int, E: int, K: int, I: int, dtype: str = F32, seed: int = 0,
                  renormalize: bool = True, sigma_w: float = 0.02) -> MoEConfig:
     return MoEConfig(f"T{T}H{H}E{E}K{K}I{I}", T, H, E, K, I, dtype, renormalize, None, seed, sigma_w)
+
+
+# ---- token log-probability / GRPO objective step --------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class GrpoConfig:
+    name: str
+    N: int                 # response tokens of the group, concatenated
+    V: int                 # vocabulary size
+    G: int                 # responses in the group
+    dtype: str             # storage type of the logits
+    clip_eps: float = 0.2
+    beta: float = 0.04
+    adv_eps: float = 1e-6
+    seed: int = 0
+    logit_scale: float = 2.5
+
+
+GRPO_CONFIGS: Dict[str, GrpoConfig] = {
+    # one 16k-token segment of log-prob recompute over the group of 8 responses of a prompt (Section 4.1),
+    # Qwen3 vocabulary
+    "logprob16k": GrpoConfig("logprob16k", 16384, 151936, 8, BF16),
+    "logprob_small": GrpoConfig("logprob_small", 300, 4096, 5, F32),
+}
+
+
+def make_grpo_inputs(cfg: GrpoConfig, rows: Optional[slice] = None) -> Dict[str, np.ndarray]:
+    """Logits ~ N(0, logit_scale^2) with the target's logit raised so that targets are likely-ish tokens, old and
+    reference log-probs near plausible values, 0/1 rewards, response lengths of a long-tailed mix.  `rows`
+    restricts the (large) logits tensor to a row range; everything else is always complete."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([cfg.seed, 101])))
+    target = rng.integers(0, cfg.V, cfg.N).astype(np.int32)
+    # response lengths: a long-tailed split of N into G parts (some may be short, none negative)
+    wts = rng.pareto(1.5, cfg.G) + 0.05 if cfg.G > 0 else np.zeros(0)
+    lens = np.floor(wts / max(wts.sum(), 1e-30) * cfg.N).astype(np.int64) if cfg.G > 0 else np.zeros(0, np.int64)
+    if cfg.G > 0:
+        lens[-1] += cfg.N - lens.sum()
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rewards = (rng.random(cfg.G) < 0.5).astype(np.float32)
+    logp_old = (-rng.gamma(2.0, 0.8, cfg.N)).astype(np.float32)
+    logp_ref = (logp_old + rng.standard_normal(cfg.N).astype(np.float32) * 0.2).astype(np.float32)
+    r0, r1 = (0, cfg.N) if rows is None else (rows.start or 0, cfg.N if rows.stop is None else rows.stop)
+    out = {"target": target, "resp_offsets": offsets, "rewards": rewards, "logp_old": logp_old, "logp_ref": logp_ref}
+    n = r1 - r0
+    chunks = []
+    for c0 in range(r0, r1, 512):                       # row blocks of 512, each its own stream: any row range
+        c1 = min(c0 + 512, r1)                          # of a 512-aligned start reproduces the same values
+        blk = c0 // 512
+        b0 = blk * 512
+        a = _normal(cfg.seed, 1000 + blk, (min(512, cfg.N - b0), cfg.V), cfg.logit_scale)
+        a[np.arange(a.shape[0]), target[b0:b0 + a.shape[0]]] += np.float32(2.0 * cfg.logit_scale)
+        chunks.append(a[c0 - b0:c1 - b0])
+    logits = np.concatenate(chunks, axis=0) if chunks else np.zeros((0, cfg.V), np.float32)
+    assert logits.shape[0] == n
+    if cfg.dtype == BF16:
+        bits = f32_to_bf16_bits(logits)
+        out["logits"] = bits
+        out["logits_f32"] = bf16_bits_to_f32(bits)
+    else:
+        out["logits"] = logits
+        out["logits_f32"] = logits
+    return out

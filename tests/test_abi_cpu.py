@@ -7,7 +7,7 @@ import re
 import pytest
 
 from paper_2511_11373_amd import build as hip_build
-from paper_2511_11373_amd import moe
+from paper_2511_11373_amd import grpo, moe
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -100,3 +100,29 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(moe, "LIB_PATH", str(tmp_path / "libmoe_ffn.so"))
     with pytest.raises(FileNotFoundError):
         moe.load_library()
+
+
+def test_grpo_symbols_and_validation(lib):
+    hdr = open(os.path.join(ROOT, "include", "grpo_loss.h")).read()
+    declared = set(re.findall(r"\b(grpo_[a-z_]+)\s*\(", hdr))
+    assert declared == set(grpo.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    vp = ctypes.c_void_p
+    a = [vp(0x1000 * (i + 1)) for i in range(12)]
+    good = grpo.GrpoShape(4, 64, 2, 0, 0.2, 0.04, 1e-6)
+    for fields, code in ((dict(N=-1), 2), (dict(V=60), 2), (dict(V=0), 2), (dict(G=-1), 2), (dict(dtype=5), 3)):
+        d = dict(N=4, V=64, G=2, dtype=0)
+        d.update(fields)
+        bad = grpo.GrpoShape(d["N"], d["V"], d["G"], d["dtype"], 0.2, 0.04, 1e-6)
+        assert lib.grpo_token_logprob(ctypes.byref(bad), a[0], a[1], a[2], None) == code
+        assert lib.grpo_objective(ctypes.byref(bad), *a[:9], None) == code
+        assert lib.grpo_logprob_objective(ctypes.byref(bad), *a[:11], None) == code
+    assert lib.grpo_token_logprob(ctypes.byref(good), None, a[1], a[2], None) == 1
+    assert lib.grpo_token_logprob(ctypes.byref(good), vp(0x1004), a[1], a[2], None) == 5
+    assert lib.grpo_objective(ctypes.byref(good), *a[:8], None, None) == 1
+    assert lib.grpo_logprob_objective(ctypes.byref(good), *a[:10], None, None) == 1
+    empty = grpo.GrpoShape(0, 64, 0, 0, 0.2, 0.04, 1e-6)
+    assert lib.grpo_token_logprob(ctypes.byref(empty), a[0], a[1], a[2], None) == 0
+    assert lib.grpo_logprob_objective(ctypes.byref(empty), *a[:11], None) == 0
+    assert lib.grpo_token_logprob(None, a[0], a[1], a[2], None) == 1

@@ -1,0 +1,103 @@
+"""GPU parity of the token log-probability / GRPO objective step against the numpy oracle (float64).
+
+Tolerances (float kernel, one pass, fast exponentials): |logp - oracle| <= 5e-5 (the online log-sum-exp rescales
+its running sum a few dozen times per thread, each rescale good to ~1e-7); token terms within 2e-4 * (1 + |term|)
+(the ratio inherits the log-prob error times |A|); response means and the objective within 2e-4 * (1 + |value|).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import grpo_oracle as go
+from paper_2511_11373_amd import grpo, moe
+from paper_2511_11373_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+LOGP_TOL = 5e-5
+REL_TOL = 2e-4
+
+
+def _dev(d, cfg):
+    lg = torch.from_numpy(d["logits"])
+    lg = (lg.view(torch.bfloat16) if cfg.dtype == wl.BF16 else lg).cuda()
+    rest = {k: torch.from_numpy(d[k]).cuda() for k in ("target", "resp_offsets", "rewards", "logp_old", "logp_ref")}
+    return lg, rest
+
+
+def _check(got, ref, what):
+    got = got.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)), what
+    assert np.all(np.abs(got - ref) <= REL_TOL * (1.0 + np.abs(ref))), (what, np.abs(got - ref).max())
+
+
+CASES = [
+    wl.GRPO_CONFIGS["logprob_small"],
+    wl.GrpoConfig("one_token", 1, 8, 1, wl.F32, seed=1),
+    wl.GrpoConfig("ragged_vocab", 67, 8 * 1237, 6, wl.BF16, seed=2),           # V/8 not a multiple of the block
+    wl.GrpoConfig("tiny_vocab", 500, 64, 9, wl.BF16, seed=3),                   # most threads see no element
+    wl.GrpoConfig("many_responses", 700, 2048, 300, wl.F32, seed=4),            # empty responses certain
+    wl.GrpoConfig("vocab_qwen", 96, 151936, 8, wl.BF16, seed=5),                # the real vocabulary, few rows
+]
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
+def test_against_oracle(cfg):
+    moe.load_library()
+    d = wl.make_grpo_inputs(cfg)
+    lg, r = _dev(d, cfg)
+    shp = grpo.make_shape(cfg.N, cfg.V, cfg.G, lg.dtype, cfg.clip_eps, cfg.beta, cfg.adv_eps)
+    o_logp, o_adv, o_term, o_mean, o_J = go.logprob_objective(d["logits_f32"], d["target"], d["logp_old"], d["logp_ref"],
+                                                              d["rewards"], d["resp_offsets"], cfg.clip_eps, cfg.beta, cfg.adv_eps)
+    # step 1 alone
+    logp = grpo.grpo_token_logprob(shp, lg, r["target"])
+    err = np.abs(logp.cpu().numpy().astype(np.float64) - o_logp).max()
+    assert err <= LOGP_TOL, err
+    # step 2 alone, fed with the oracle's log-probs (rounded to float) so that it is checked on its own
+    lp32 = o_logp.astype(np.float32)
+    a2, t2, m2, j2 = go.objective(lp32, d["logp_old"], d["logp_ref"], d["rewards"], d["resp_offsets"], cfg.clip_eps, cfg.beta, cfg.adv_eps)
+    adv, term, mean, obj = grpo.grpo_objective(shp, torch.from_numpy(lp32).cuda(), r["logp_old"], r["logp_ref"], r["rewards"],
+                                               r["resp_offsets"])
+    _check(adv, a2, "advantage")
+    _check(term, t2, "token terms")
+    _check(mean, m2, "response means")
+    _check(obj, np.array([j2]), "objective")
+    # fused
+    logp3, adv3, term3, mean3, obj3 = grpo.grpo_logprob_objective(shp, lg, r["target"], r["logp_old"], r["logp_ref"], r["rewards"],
+                                                                  r["resp_offsets"])
+    assert torch.equal(logp3, logp)
+    _check(adv3, o_adv, "advantage (fused)")
+    _check(term3, o_term, "token terms (fused)")
+    _check(mean3, o_mean, "response means (fused)")
+    _check(obj3, np.array([o_J]), "objective (fused)")
+    # run to run identical
+    again = grpo.grpo_logprob_objective(shp, lg, r["target"], r["logp_old"], r["logp_ref"], r["rewards"], r["resp_offsets"])
+    assert all(torch.equal(a, b) for a, b in zip(again, (logp3, adv3, term3, mean3, obj3)))
+
+
+def test_closed_forms_and_extremes():
+    moe.load_library()
+    V = 4096
+    shp = grpo.make_shape(3, V, 1, torch.float32)
+    lg = torch.full((3, V), 1.75, dtype=torch.float32, device="cuda")
+    lg[1] += 3.0e4                                       # a large common offset must cancel
+    lg[2, 7] = 9.0e4                                     # one entry dominates completely
+    tgt = torch.tensor([0, V - 1, 7], dtype=torch.int32, device="cuda")
+    lp = grpo.grpo_token_logprob(shp, lg, tgt).cpu().numpy()
+    assert abs(lp[0] + np.log(V)) < 1e-5 and abs(lp[1] + np.log(V)) < 1e-5 and abs(lp[2]) < 1e-6
+
+
+def test_empty_and_bad_arguments():
+    lib = moe.load_library()
+    shp = grpo.make_shape(0, 64, 0, torch.float32)
+    x = torch.zeros((1, 64), dtype=torch.float32, device="cuda")
+    t = torch.zeros(4, dtype=torch.int32, device="cuda")
+    f = torch.full((4,), 5.0, dtype=torch.float32, device="cuda")
+    out = (f.clone(), f.clone(), f.clone(), f.clone(), f.clone())
+    grpo.grpo_logprob_objective(shp, x, t, f, f, f, t, out=out)
+    torch.cuda.synchronize()
+    assert all(torch.all(o == 5.0) for o in out)         # nothing was enqueued
+    bad = grpo.make_shape(4, 60, 1, torch.float32)
+    with pytest.raises(moe.MoeError) as ei:
+        grpo.grpo_token_logprob(bad, x, t)
+    assert ei.value.code == 2

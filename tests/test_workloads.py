@@ -9,6 +9,7 @@ def test_bf16_rounding_matches_torch_and_round_trips():
     rng = np.random.default_rng(0)
     a = (rng.standard_normal(100000) * 10.0 ** rng.integers(-6, 4, 100000)).astype(np.float32)
     bits = wl.f32_to_bf16_bits(a)
+    assert np.array_equal(bits, wl.f32_to_bf16_bits_numpy(a))
     ref = torch.from_numpy(a).to(torch.bfloat16)
     assert np.array_equal(bits, ref.view(torch.uint16).numpy())
     assert np.array_equal(wl.bf16_bits_to_f32(bits), ref.float().numpy())
@@ -36,3 +37,15 @@ def test_zipf_target_and_bias():
     b = wl.zipf_router_bias(cfg)
     assert b.shape == (cfg.E,) and b.dtype == np.float32 and np.array_equal(b, wl.zipf_router_bias(cfg))
     assert b.max() - b.min() > 2.0
+
+
+def test_grpo_inputs():
+    cfg = wl.GRPO_CONFIGS["logprob_small"]
+    d = wl.make_grpo_inputs(cfg)
+    assert d["logits"].shape == (cfg.N, cfg.V) and d["target"].min() >= 0 and d["target"].max() < cfg.V
+    off = d["resp_offsets"]
+    assert off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0) and off.shape == (cfg.G + 1,)
+    part = wl.make_grpo_inputs(cfg, rows=slice(100, 250))
+    assert np.array_equal(part["logits"], d["logits"][100:250]) and np.array_equal(part["target"], d["target"])
+    big = wl.GRPO_CONFIGS["logprob16k"]
+    assert big.V % 8 == 0 and big.N == 16384 and big.G == 8
