@@ -58,10 +58,86 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="decode64",
-                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k"])
+                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
+
+
+def bench_logprob(args):
+    """The next row of the path: token log-probabilities + GRPO objective over one 16k-token group (Eq. 1-3).
+    One step = one grpo_logprob_objective call; bound by reading the [N, V] logits once from HBM."""
+    import torch
+    from paper_2511_11373_amd import grpo
+    from paper_2511_11373_amd import workloads as wl
+    cfg = wl.GRPO_CONFIGS["logprob16k"]
+    steps = args.steps if args.steps is not None else 50
+    warmup = args.warmup if args.warmup is not None else 5
+    d = wl.make_grpo_inputs(cfg, rows=slice(0, 512))          # everything but the logits; 512 host rows for the oracle
+    dev = {k: torch.from_numpy(d[k]).cuda() for k in ("target", "resp_offsets", "rewards", "logp_old", "logp_ref")}
+    # the 5 GB logits tensor is drawn on the device (same law as the host generator: N(0, s^2), target raised by 2s);
+    # its first 512 rows are overwritten with the host generator's so that the oracle sees identical values
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    logits = torch.empty((cfg.N, cfg.V), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, cfg.N, 1024):
+        blk = torch.randn((1024, cfg.V), device="cuda", generator=gen) * cfg.logit_scale
+        idx = dev["target"][r0:r0 + 1024].long()
+        blk[torch.arange(1024, device="cuda"), idx] += 2.0 * cfg.logit_scale
+        logits[r0:r0 + 1024] = blk.to(torch.bfloat16)
+    logits[:512] = torch.from_numpy(d["logits"]).view(torch.bfloat16).cuda()
+    shp = grpo.make_shape(cfg.N, cfg.V, cfg.G, logits.dtype, cfg.clip_eps, cfg.beta, cfg.adv_eps)
+    out = grpo.grpo_logprob_objective(shp, logits, dev["target"], dev["logp_old"], dev["logp_ref"], dev["rewards"], dev["resp_offsets"])
+
+    def step():
+        grpo.grpo_logprob_objective(shp, logits, dev["target"], dev["logp_old"], dev["logp_ref"], dev["rewards"],
+                                    dev["resp_offsets"], out=out)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    # the dominant kernel alone (grpo_token_logprob is exactly that kernel), HIP events on the launch stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    lp = grpo.grpo_token_logprob(shp, logits, dev["target"])
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        grpo.grpo_token_logprob(shp, logits, dev["target"])
+    e1.record()
+    torch.cuda.synchronize()
+    k_ms = e0.elapsed_time(e1) / steps
+    nbytes = cfg.N * cfg.V * 2 + cfg.N * 8
+    ach = nbytes / (k_ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import grpo_oracle as go
+        n = 512
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < args.cpu_seconds:
+            o_logp = go.token_logprob(d["logits_f32"], d["target"][:n])
+            reps += 1
+        dt = time.perf_counter() - c0
+        err = float(np.abs(out[0][:n].cpu().numpy().astype(np.float64) - o_logp).max())
+        cpu = {"value": round(n * reps / dt, 2), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"log-probs of the first {n} of {cfg.N} rows, {reps} pass(es), {dt:.1f} s (numpy, float64)",
+               "max_abs_logp_err_gpu_vs_oracle": err}
+    rec = {
+        "metric": "log-prob + GRPO-objective tokens/s + % HBM BW", "value": round(cfg.N / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": cfg.N, "vocab": cfg.V, "responses": cfg.G, "logits_dtype": "bf16"},
+        "roofline": {"bound": "hbm", "kernel": "logprob_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": int(nbytes), "avg_launch_ms": round(k_ms, 5)},
+        "cpu_baseline": cpu,
+        "objective": float(out[4].item()),
+    }
+    print(json.dumps(rec))
 
 
 def main():
@@ -78,6 +154,8 @@ def main():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(3)
     moe.load_library()          # raises if the HIP library is not built: there is no fallback
+    if args.workload == "logprob16k":
+        return bench_logprob(args)
     cfg = wl.CONFIGS[args.workload]
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[cfg.name]
     warmup = args.warmup if args.warmup is not None else max(5, steps // 10)

@@ -136,30 +136,44 @@ __global__ __launch_bounds__(256) void term_kernel(const float *__restrict__ log
     term_out[t] = surrogate_term(logp[t], logp_old[t], logp_ref[t], adv[response_of(off, G, t)], clip_eps, beta);
 }
 
-// response means and the objective: one block, wave w owns responses w, w+16, ...; lanes stride over a
-// response's tokens, a butterfly adds the 64 partial sums; thread 0 adds the means in response order.
+// response means and the objective: one block of 16 waves.  W waves share a response (W = 16 for one response,
+// 1 from 16 responses on); every lane strides over its share of the response's tokens, a butterfly adds the 64
+// partial sums, the W wave sums are added in wave order, and thread 0 adds the means in response order.
 __global__ __launch_bounds__(1024) void objective_kernel(const float *__restrict__ term, const int32_t *__restrict__ off, int G,
                                                          float *__restrict__ resp_mean, float *__restrict__ objective) {
     __shared__ float part[16];
+    __shared__ float jsum;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    float mine = 0.f;                       // sum of the means of this wave's responses, in response order
-    for (int i = wave; i < G; i += 16) {
-        const int b = off[i], e = off[i + 1];
+    int W = 16;
+    while (W > 1 && 16 / W < G) W >>= 1;
+    const int per_round = 16 / W, sub = wave % W;
+    if (threadIdx.x == 0) jsum = 0.f;
+    for (int i0 = 0; i0 < G; i0 += per_round) {
+        const int i = i0 + wave / W;
         float a = 0.f;
-        for (int t = b + lane; t < e; t += 64) a += term[t];
+        int b = 0, e = 0;
+        if (i < G) {
+            b = off[i];
+            e = off[i + 1];
+            for (int t = b + sub * 64 + lane; t < e; t += W * 64) a += term[t];
 #pragma unroll
-        for (int k = 32; k >= 1; k >>= 1) a += __shfl_xor(a, k, 64);
-        const float mean = e > b ? a / (float)(e - b) : 0.f;
-        if (lane == 0) resp_mean[i] = mean;
-        mine += mean;
+            for (int k = 32; k >= 1; k >>= 1) a += __shfl_xor(a, k, 64);
+        }
+        if (lane == 0) part[wave] = a;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int r = 0; r < per_round && i0 + r < G; ++r) {
+                float sum = 0.f;
+                for (int j = 0; j < W; ++j) sum += part[r * W + j];
+                const int n = off[i0 + r + 1] - off[i0 + r];
+                const float mean = n > 0 ? sum / (float)n : 0.f;
+                resp_mean[i0 + r] = mean;
+                jsum += mean;
+            }
+        }
+        __syncthreads();
     }
-    if (lane == 0) part[wave] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float j = 0.f;
-        for (int w = 0; w < 16; ++w) j += part[w];
-        objective[0] = G > 0 ? j / (float)G : 0.f;
-    }
+    if (threadIdx.x == 0) objective[0] = G > 0 ? jsum / (float)G : 0.f;
 }
 
 static moe_status_t check_grpo(const grpo_shape_t *s) {

@@ -101,3 +101,32 @@ def test_empty_and_bad_arguments():
     with pytest.raises(moe.MoeError) as ei:
         grpo.grpo_token_logprob(bad, x, t)
     assert ei.value.code == 2
+
+
+def test_full_size_on_sampled_rows():
+    """The benchmark's shape (16384 x 151936, bf16): the 5 GB of logits are drawn on the device with torch's seeded
+    generator (plumbing, not the path under test); log-probs are compared on sampled rows copied back to the
+    oracle, and the objective against the oracle's Eq. 1-3 applied to the kernel's own log-probs."""
+    moe.load_library()
+    cfg = wl.GRPO_CONFIGS["logprob16k"]
+    d = wl.make_grpo_inputs(cfg, rows=slice(0, 0))
+    r = {k: torch.from_numpy(d[k]).cuda() for k in ("target", "resp_offsets", "rewards", "logp_old", "logp_ref")}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    logits = torch.empty((cfg.N, cfg.V), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, cfg.N, 2048):
+        logits[r0:r0 + 2048] = (torch.randn((2048, cfg.V), device="cuda", generator=gen) * cfg.logit_scale).to(torch.bfloat16)
+    shp = grpo.make_shape(cfg.N, cfg.V, cfg.G, logits.dtype, cfg.clip_eps, cfg.beta, cfg.adv_eps)
+    logp, adv, term, mean, obj = grpo.grpo_logprob_objective(shp, logits, r["target"], r["logp_old"], r["logp_ref"], r["rewards"],
+                                                             r["resp_offsets"])
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, cfg.N - 1], rng.integers(0, cfg.N, 62)]))
+    sample = logits[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    o_logp = go.token_logprob(sample, d["target"][rows])
+    assert np.abs(logp.cpu().numpy()[rows].astype(np.float64) - o_logp).max() <= LOGP_TOL
+    a2, t2, m2, j2 = go.objective(logp.cpu().numpy(), d["logp_old"], d["logp_ref"], d["rewards"], d["resp_offsets"], cfg.clip_eps,
+                                  cfg.beta, cfg.adv_eps)
+    _check(adv, a2, "advantage")
+    _check(term, t2, "token terms")
+    _check(mean, m2, "response means")
+    _check(obj, np.array([j2]), "objective")
