@@ -55,6 +55,29 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void *)p;
 }
 
+template <bool B>
+struct FullTile { static constexpr bool value = B; };
+
+// Which of the next stage's 16 global->LDS loads follows MFMA m of k step ks (-1: none).
+#ifndef MOE_BIG_LOADPLAN
+#define MOE_BIG_LOADPLAN 3
+#endif
+// Plans 0-2 load the next stage during the first k steps of the current one; plan 3 loads the stage after
+// the next during the last k step, right behind the barrier that frees the buffer, which leaves three k steps
+// for the data to arrive instead of one or two.
+__device__ constexpr int big_load_slot(int ks, int m) {
+#if MOE_BIG_LOADPLAN == 0
+    return ks == 0 ? m : -1;
+#elif MOE_BIG_LOADPLAN == 1
+    return (ks < 2 && m >= 8) ? ks * 8 + m - 8 : -1;
+#elif MOE_BIG_LOADPLAN == 2
+    return (ks < 2 && (m & 1)) ? ks * 8 + (m >> 1) : -1;
+#else
+    return ks == 3 ? m : -1;
+#endif
+}
+constexpr bool big_load_two_ahead = MOE_BIG_LOADPLAN == 3;
+
 __device__ __forceinline__ float silu_mul_f(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
 template <bool GATE_UP>
@@ -68,7 +91,6 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
-    __shared__ __attribute__((aligned(256))) unsigned char Sink[4 * 512];   // landing area of the L2 warm-up loads
 
     // ---- which tile --------------------------------------------------------------------------
     const int total = tile_map[2 * max_tiles] * n_wtiles;
@@ -81,40 +103,31 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int row_end = off[e + 1];
     const int wrow0 = wtile * (GATE_UP ? BW / 2 : BW);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: LDS destinations stay in scalar registers
     const int ww = wave & 1, wt = wave >> 1;
     // The 256 token rows are 8 sub-tiles of 32; token-wave wt owns sub-tiles wt, wt+2, wt+4, wt+6, so a
     // short (ragged) tile is split evenly between the two token waves.  nb = live sub-tiles of this wave.
     const int nsub = min(8, (row_end - row0 + 31) >> 5);
     const int nb = max(0, min(4, (nsub - wt + 1) >> 1));
 
-    // ---- global sources of this thread's 8 + 8 pieces per stage ---------------------------------
-    // load instruction i of this wave fills LDS rows (i*4 + wave)*8 .. +8; lane -> (row lane/8, position lane%8).
-    // (row >> 1) & 7 does not depend on i, so neither does the piece a lane fetches.
-    const int lrow = wave * 8 + (lane >> 3);                      // LDS row of instruction 0
+    // ---- global sources of this thread's 16 pieces per stage ------------------------------------
+    // load 2*i (weights) and 2*i+1 (tokens) of this wave fill LDS rows (i*4 + wave)*8 .. +8 of their operand;
+    // lane -> (row lane/8, position lane%8).  (row >> 1) & 7 does not depend on i, so neither does the piece
+    // a lane fetches.
+    const int lrow = wave * 8 + (lane >> 3);                      // LDS row of pair 0
     const int piece = (lane & 7) ^ ((lrow >> 1) & 7);
-    // weights: rows are a fixed stride apart (the launcher guarantees whole weight tiles)
-    const bf16_t *wbase0 = w0 + ((size_t)e * NW + wrow0 + lrow) * KD + piece * 8;
-    const bf16_t *wbase1 = GATE_UP ? w1 + ((size_t)e * NW + wrow0 + lrow) * KD + piece * 8 : wbase0;
-    const size_t wstride = (size_t)32 * KD;
-    // token rows: gathered, clamped to the expert's last row (results of clamped rows are never stored)
-    int xrow[8];
+    const bf16_t *src[16];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+        // weights: rows are a fixed stride apart (the launcher guarantees whole weight tiles)
+        const bf16_t *wm = GATE_UP && i >= 4 ? w1 : w0;
+        const int wr = GATE_UP ? (i & 3) * 32 + lrow : i * 32 + lrow;
+        src[2 * i] = wm + ((size_t)e * NW + wrow0 + wr) * KD + piece * 8;
+        // token rows: gathered, clamped to the expert's last row (results of clamped rows are never stored)
         int xr = row0 + i * 32 + lrow;
         xr = xr < row_end ? xr : row_end - 1;
-        xrow[i] = row_map ? row_map[xr] / K_assign : xr;
-    }
-    const bf16_t *xbase = xrows + piece * 8;
-    // L2 warm-up: one 128-byte line of a later stage per thread and operand (row (lane%8)*32 + lrow)
-    const bf16_t *pf_w, *pf_x;
-    {
-        const int prow = (lane & 7) * 32 + lrow;
-        if (GATE_UP) pf_w = (prow < 128 ? w0 : w1) + ((size_t)e * NW + wrow0 + (prow & 127)) * KD;
-        else pf_w = w0 + ((size_t)e * NW + wrow0 + prow) * KD;
-        int xr = row0 + prow;
-        xr = xr < row_end ? xr : row_end - 1;
-        pf_x = xrows + (size_t)(row_map ? row_map[xr] / K_assign : xr) * KD;
+        src[2 * i + 1] = xrows + (size_t)(row_map ? row_map[xr] / K_assign : xr) * KD + piece * 8;
     }
 
     f32x16 acc[4][4];
@@ -125,18 +138,9 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // one weight piece and one token piece per thread: pair i fills LDS rows (i*4 + wave)*8 .. +8 of both operands
-    auto issue_pair = [&](unsigned char *Ws, unsigned char *Xs, int k0, int i) {
-        const bf16_t *wp = GATE_UP ? (i < 4 ? wbase0 + i * wstride : wbase1 + (i - 4) * wstride) : wbase0 + i * wstride;
-        __builtin_amdgcn_global_load_lds((gbl_void *)(wp + k0), (lds_void *)(Ws + (i * 4 + wave) * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_void *)(xbase + (size_t)xrow[i] * KD + k0),
-                                         (lds_void *)(Xs + (i * 4 + wave) * 1024), 16, 0, 0);
-    };
-    const int k_last = KD - BK;
-    auto warm = [&](int k0) {        // two 4-byte loads per thread whose only purpose is to pull lines into L2
-        k0 = k0 < k_last ? k0 : k_last;
-        __builtin_amdgcn_global_load_lds((gbl_void *)(pf_w + k0), (lds_void *)(Sink + wave * 512), 4, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_void *)(pf_x + k0), (lds_void *)(Sink + wave * 512 + 256), 4, 0, 0);
+    auto issue = [&](unsigned char *Ws, unsigned char *Xs, int k0, int j) {
+        unsigned char *dst = ((j & 1) ? Xs : Ws) + ((j >> 1) * 4 + wave) * 1024;
+        __builtin_amdgcn_global_load_lds((gbl_void *)(src[j] + k0), (lds_void *)dst, 16, 0, 0);
     };
     // operand addresses inside a stage: lane (row l%32, half l/32); k step ks uses pieces 2*ks + half.
     // Tile bases are multiples of 32 rows, so the swizzle term only depends on the lane.
@@ -148,78 +152,92 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const unsigned b_base = wt * 32 * ROWB;
     constexpr int A1 = 32 * ROWB, A2 = GATE_UP ? 128 * ROWB : 64 * ROWB, A3 = GATE_UP ? 160 * ROWB : 96 * ROWB;
     bf16x8 aop[2][4], bop[2][4];
-    auto read_ops = [&](unsigned ws, unsigned xs, int ks, int set) {
-        const unsigned wa = ws + a_base + kpos[ks], xa = xs + b_base + kpos[ks];
-        aop[set][0] = lds_read_b128<0>(wa);
-        bop[set][0] = lds_read_b128<0>(xa);
-        bop[set][1] = lds_read_b128<64 * ROWB>(xa);
-        aop[set][1] = lds_read_b128<A1>(wa);
-        bop[set][2] = lds_read_b128<128 * ROWB>(xa);
-        bop[set][3] = lds_read_b128<192 * ROWB>(xa);
-        aop[set][2] = lds_read_b128<A2>(wa);
-        aop[set][3] = lds_read_b128<A3>(wa);
+    // the 8 operand reads of a k step, in the order the MFMAs first need them
+    auto read_one = [&](unsigned wa, unsigned xa, int set, int q) {
+        switch (q) {
+            case 0: aop[set][0] = lds_read_b128<0>(wa); break;
+            case 1: bop[set][0] = lds_read_b128<0>(xa); break;
+            case 2: aop[set][1] = lds_read_b128<A1>(wa); break;
+            case 3: aop[set][2] = lds_read_b128<A2>(wa); break;
+            case 4: aop[set][3] = lds_read_b128<A3>(wa); break;
+            case 5: bop[set][1] = lds_read_b128<64 * ROWB>(xa); break;
+            case 6: bop[set][2] = lds_read_b128<128 * ROWB>(xa); break;
+            default: bop[set][3] = lds_read_b128<192 * ROWB>(xa); break;
+        }
     };
-    auto mfma16 = [&](int set) {
+    // One 16-wide k step: 16 MFMAs out of operand set ks&1.  A wave is alone on its SIMD, so an instruction
+    // that is not an MFMA only comes for free in the shadow of the MFMA issued just before it (the matrix
+    // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and this k step's
+    // share of the next stage's 16 global->LDS loads are therefore dealt out one per MFMA.
+    auto kstep = [&](auto full_c, int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wn,
+                     unsigned char *Xn, int k_next) {
+        constexpr bool FULL = decltype(full_c)::value;
+        const int set = ks & 1;
+        const unsigned wa = wrd + a_base + kpos[ks_rd], xa = xrd + b_base + kpos[ks_rd];
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-            if (b < nb) {
+        for (int m = 0; m < 16; ++m) {
+            const int b = m >> 2, a = m & 3;
+            if (FULL) {
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+            } else if (a == 0 && b < nb) {
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
+                for (int a2 = 0; a2 < 4; ++a2)
+                    acc[a2][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a2], bop[set][b], acc[a2][b], 0, 0, 0);
             }
-    };
-    // the same with one load pair slipped in after every four MFMAs: the address unit works through the
-    // loads in the shadow of the matrix pipe instead of stalling all four waves at once
-    auto mfma16_load = [&](int set, bool load, unsigned char *Ws, unsigned char *Xs, int k0, int i0) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (b < nb) {
-#pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a], bop[set][b], acc[a][b], 0, 0, 0);
-            }
-            if (load) issue_pair(Ws, Xs, k0, i0 + b);
+            if (m < 8) read_one(wa, xa, set ^ 1, m);
+            const int j = big_load_slot(ks, m);
+            if (j >= 0) issue(Wn, Xn, k_next, j);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // ---- main loop ------------------------------------------------------------------------------------
-    // Two LDS stages, one block barrier per stage.  While stage kt is multiplied out of one buffer, the 16
-    // loads of stage kt+1 are issued into the other, interleaved with the MFMAs of the first two k steps; the
-    // last two k steps (32 MFMAs) cover their latency, helped by warm-up loads that pull the lines of stage
-    // kt+3 into L2.  Operand registers are double-buffered per 16-wide k step.
-    // Loads retire in order: at the end of a stage only the 2 warm-up loads may still be in flight (vmcnt(2)).
+    // Two LDS stages, one block barrier per stage.  Operand registers are double-buffered per 16-wide k step.
+    // The barrier sits in front of the last k step of a stage: by then this wave has read everything it needs
+    // from the current buffer and its own loads into the other buffer have landed, so behind the barrier the
+    // current buffer is free in every wave and the other one is complete.  The last k step therefore reads the
+    // first operands of the next stage and issues the 16 loads of the stage after the next into the buffer
+    // just freed; they have the three following k steps (about a microsecond) to arrive, which is what a miss
+    // to HBM takes under load.  The last two stages reload the final k tile instead of branching around the loads.
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
+    const int k_last = KD - BK;
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) issue_pair(WsA, XsA, 0, i);
-    warm(BK);
-    warm(2 * BK);
-    MOE_WAIT_VMCNT(4);
-    __builtin_amdgcn_s_barrier();
-    read_ops(wsA, xsA, 0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool odd = kt & 1, more = kt + 1 < nk;
-        const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
-        const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
-        unsigned char *Wn = odd ? WsA : WsB, *Xn = odd ? XsA : XsB;
-        const int k_next = (kt + 1) * BK;
-        read_ops(wcur, xcur, 1, 1);
-        wait_lds_reads<8>(aop[0], bop[0]);
-        mfma16_load(0, more, Wn, Xn, k_next, 0);
-        read_ops(wcur, xcur, 2, 0);
-        wait_lds_reads<8>(aop[1], bop[1]);
-        mfma16_load(1, more, Wn, Xn, k_next, 4);
-        read_ops(wcur, xcur, 3, 1);
-        wait_lds_reads<8>(aop[0], bop[0]);
-        mfma16(0);
-        warm((kt + 3) * BK);
-        wait_lds_reads<0>(aop[1], bop[1]);       // every read of the current stage has landed ...
-        MOE_WAIT_VMCNT(2);                       // ... and so has every load of the next one
-        __builtin_amdgcn_s_barrier();            // ... in every wave
-        if (more) read_ops(wnxt, xnxt, 0, 0);
-        mfma16(1);
+    for (int j = 0; j < 16; ++j) issue(WsA, XsA, 0, j);
+    if (big_load_two_ahead) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) issue(WsB, XsB, min(BK, k_last), j);
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    } else {
+        MOE_WAIT_VMCNT(0);
     }
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
+    auto run = [&](auto full_c) {
+#pragma unroll 1
+        for (int kt = 0; kt < nk; ++kt) {
+            const bool odd = kt & 1;
+            const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
+            const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
+            // destination and k offset of the loads issued in this iteration
+            unsigned char *Wl = (odd != big_load_two_ahead) ? WsA : WsB, *Xl = (odd != big_load_two_ahead) ? XsA : XsB;
+            const int k_load = min((kt + (big_load_two_ahead ? 2 : 1)) * BK, k_last);
+            wait_lds_reads<0>(aop[0], bop[0]);
+            kstep(full_c, 0, wcur, xcur, 1, Wl, Xl, k_load);
+            wait_lds_reads<0>(aop[1], bop[1]);
+            kstep(full_c, 1, wcur, xcur, 2, Wl, Xl, k_load);
+            wait_lds_reads<0>(aop[0], bop[0]);
+            kstep(full_c, 2, wcur, xcur, 3, Wl, Xl, k_load);
+            wait_lds_reads<0>(aop[1], bop[1]);
+            MOE_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();
+            kstep(full_c, 3, wnxt, xnxt, 0, Wl, Xl, k_load);
+        }
+    };
+    if (nsub == 8) run(FullTile<true>{});
+    else run(FullTile<false>{});
+    wait_lds_reads<0>(aop[0], bop[0]);
     MOE_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
 
