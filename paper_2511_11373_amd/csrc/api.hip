@@ -1,6 +1,7 @@
 // C ABI of the MoE FFN library: argument validation (host only, before any HIP
 // call), workspace carving, and the launch sequences.
 #include "moe_internal.hpp"
+#include <algorithm>
 
 namespace moe {
 
@@ -37,7 +38,8 @@ Workspace carve_workspace(const moe_shape_t &s, void *base) {
     take(cur, w.row_to_assign, sizeof(int32_t) * n);
     take(cur, w.assign_to_row, sizeof(int32_t) * n);
     take(cur, w.chunk_base, sizeof(int32_t) * nchunks * s.E);
-    take(cur, w.tile_map, sizeof(int32_t) * (2 * max_tiles + 4));
+    // (expert, first row) pairs plus a count for the tiled kernel, or 16-byte entries of 256-row tiles in 8 per-XCD lists
+    take(cur, w.tile_map, std::max(sizeof(int32_t) * (2 * max_tiles + 4), (size_t)16 * (n / 256 + s.E + 8)));
     take(cur, w.act, sizeof(bf16_t) * n * s.I);
     void *y = nullptr;
     take(cur, y, elt_size(s) * n * s.H);

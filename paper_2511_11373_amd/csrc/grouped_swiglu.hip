@@ -194,13 +194,11 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
         }
 }
 
-// large-batch bf16 variant (grouped_swiglu_big.hip)
+// large-batch bf16 variant (grouped_swiglu_big.hip); builds its own per-XCD row-tile list in `tile_map`
 bool big_gemm_applicable(const moe_shape_t &s);
-int big_tile_rows();
 hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
                                      const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
-                                     bf16_t *act, const int32_t *tile_map, int max_tiles, bf16_t *y_perm,
-                                     hipStream_t st, Probe *probe);
+                                     bf16_t *act, int32_t *tile_map, bf16_t *y_perm, hipStream_t st, Probe *probe);
 
 // decode-sized bf16 variant (grouped_swiglu_stream.hip); needs no row-tile list
 bool stream_gemm_applicable(const moe_shape_t &s);
@@ -214,8 +212,8 @@ constexpr int kWW = 2, kWT = 2, kMW = 1, kMT = 1;      // wave grid and MFMA til
 #endif
 constexpr int kBK = MOE_SMALL_BK;
 int gemm_tile_rows(const moe_shape_t &s) {
-    if (stream_gemm_applicable(s)) return 0;      // no tile list
-    return big_gemm_applicable(s) ? big_tile_rows() : kWT * kMT * 32;
+    if (stream_gemm_applicable(s) || big_gemm_applicable(s)) return 0;      // no tile list, or one of their own
+    return kWT * kMT * 32;
 }
 int gemm_max_tiles(const moe_shape_t &s) {
     const int n = s.T * s.K;
@@ -234,6 +232,8 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
             probe_mark(probe);
             return launch_grouped_swiglu_stream(s, x_rows, row_map, off, wg, wu, wd, act, y_perm, st, probe);
         }
+        if (big_gemm_applicable(s))
+            return launch_grouped_swiglu_big(s, x_rows, row_map, off, wg, wu, wd, act, tile_map, y_perm, st, probe);
     }
     const int max_tiles = gemm_max_tiles(s);
     hipError_t err = hipSuccess;
@@ -243,10 +243,6 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
         if (err != hipSuccess) return err;
     }
     probe_mark(probe);
-    if constexpr (sizeof(S) == 2) {
-        if (big_gemm_applicable(s))
-            return launch_grouped_swiglu_big(s, x_rows, row_map, off, wg, wu, wd, act, tile_map, max_tiles, y_perm, st, probe);
-    }
     hipLaunchKernelGGL((grouped_gemm_kernel<S, S, bf16_t, true, WW, WT, MW, MT, kBK>), dim3(max_tiles, (s.I + BW - 1) / BW),
                        dim3(WW * WT * 64), 0, st, x_rows, row_map, s.K, off, tile_map, max_tiles, wg, wu, act, s.H, s.I);
     err = hipGetLastError();

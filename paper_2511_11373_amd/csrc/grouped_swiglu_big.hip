@@ -12,9 +12,11 @@
 // position fetches the matching piece from global memory, so every 8 lanes still read one full
 // 128-byte line.
 //
-// Row tiles are walked in a list (expert, first row); the flattened (row tile, weight tile) index is
-// remapped so that each XCD (blocks are dealt round-robin to the 8 XCDs) works on a contiguous range
-// of the list: the blocks that share an expert's weights and a row tile's tokens share one L2.
+// Row tiles (expert, first row, end of the expert's rows) come from a list that a small kernel writes
+// once per call, already split per XCD: blocks are dealt round-robin to the 8 XCDs, block b is slot b/8
+// of XCD b%8, and XCD x owns a contiguous eighth of the row tiles, each with all its weight tiles, so
+// that the blocks sharing an expert's weights and a row tile's tokens run behind one L2.  A block finds
+// its tile with one 16-byte load at an address that depends on the block index alone.
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -78,14 +80,15 @@ __device__ constexpr int big_load_slot(int ks, int m) {
 }
 constexpr bool big_load_two_ahead = MOE_BIG_LOADPLAN == 3;
 
-__device__ __forceinline__ float silu_mul_f(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+// silu(g)*u with the hardware reciprocal (1 ulp): far inside the bf16 rounding that follows
+__device__ __forceinline__ float silu_mul_f(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
 
 template <bool GATE_UP>
 __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const bf16_t *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
-    const int32_t *__restrict__ off, const int32_t *__restrict__ tile_map, int max_tiles,
+    const i32x4 *__restrict__ tile_list, int tiles_per_xcd,
     const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1, bf16_t *__restrict__ outp, int KD, int NW,
-    int n_wtiles) {
+    int n_wtiles, int n_rows) {
     using namespace big;
     __shared__ __attribute__((aligned(1024))) unsigned char WsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
@@ -93,14 +96,11 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
 
     // ---- which tile --------------------------------------------------------------------------
-    const int total = tile_map[2 * max_tiles] * n_wtiles;
-    const int per_xcd = (total + 7) >> 3;
     const int slot = blockIdx.x >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || logical >= total) return;
-    const int rtile = logical / n_wtiles, wtile = logical - rtile * n_wtiles;
-    const int e = tile_map[2 * rtile], row0 = tile_map[2 * rtile + 1];
-    const int row_end = off[e + 1];
+    const int wtile = slot % n_wtiles;
+    const i32x4 entry = tile_list[(blockIdx.x & 7) * tiles_per_xcd + slot / n_wtiles];
+    const int e = entry[0], row0 = entry[1], row_end = entry[2];
+    if (e < 0) return;
     const int wrow0 = wtile * (GATE_UP ? BW / 2 : BW);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -124,9 +124,11 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
         const bf16_t *wm = GATE_UP && i >= 4 ? w1 : w0;
         const int wr = GATE_UP ? (i & 3) * 32 + lrow : i * 32 + lrow;
         src[2 * i] = wm + ((size_t)e * NW + wrow0 + wr) * KD + piece * 8;
-        // token rows: gathered, clamped to the expert's last row (results of clamped rows are never stored)
+        // token rows: gathered.  Rows past the expert's end belong to the next expert (or are clamped to the
+        // last row there is): they are multiplied like the others and never stored, and not having to know
+        // the expert's end here lets the gather start one memory round trip earlier.
         int xr = row0 + i * 32 + lrow;
-        xr = xr < row_end ? xr : row_end - 1;
+        xr = xr < n_rows ? xr : n_rows - 1;
         src[2 * i + 1] = xrows + (size_t)(row_map ? row_map[xr] / K_assign : xr) * KD + piece * 8;
     }
 
@@ -249,9 +251,12 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     constexpr int TROW = 32 * 4 + 16;                    // bytes per token row of a 32x32 float tile (padded)
     constexpr int TILEB = 32 * TROW;
     constexpr int LPR = GATE_UP ? 8 : 16;                // lanes per token row on the way out
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        if (b >= nb) continue;
+    auto wave_sync = [&]() {      // orders this wave's LDS traffic across its lanes (LDS serves a wave in order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto put_tiles = [&](int b) {
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -259,35 +264,53 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                 f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
                 *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
             }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    constexpr int NP = 32 * LPR / 64;                    // passes over a sub-tile: 64 / LPR tokens each
+    constexpr int NV = GATE_UP ? 4 : 2;                  // 16-byte LDS reads per pass
+    const int c = lane % LPR;                            // 8-feature piece of this lane
+    const int at = c >> 2, fi = (c & 3) * 8;             // accumulator tile and first feature inside it
+    const int f = wrow0 + (GATE_UP ? ww * 64 : ww * 128) + c * 8;
+    if (nb > 0) put_tiles(0);
 #pragma unroll
-        for (int p = 0; p < 32 * LPR / 64; ++p) {
+    for (int b = 0; b < 4; ++b) {
+        if (b >= nb) break;
+        wave_sync();
+        // all reads of the sub-tile first (one LDS latency per sub-tile instead of one per pass) ...
+        f32x4 v[NP][NV];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
             const int n = p * (64 / LPR) + lane / LPR;    // token inside the 32-token sub-tile
-            const int c = lane % LPR;                     // 8-feature piece
-            const int at = c >> 2, fi = (c & 3) * 8;      // accumulator tile and first feature inside it
             const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
-            const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gp), g1 = *reinterpret_cast<const f32x4 *>(gp + 16);
+            v[p][0] = *reinterpret_cast<const f32x4 *>(gp);
+            v[p][1] = *reinterpret_cast<const f32x4 *>(gp + 16);
+            if (GATE_UP) {
+                v[p][2] = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB);
+                v[p][3] = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB + 16);
+            }
+        }
+        wave_sync();
+        // ... then the next sub-tile's accumulators go in behind them while this one is finished and stored
+        if (b + 1 < nb) put_tiles(b + 1 < 4 ? b + 1 : 3);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int n = p * (64 / LPR) + lane / LPR;
             const int row = row0 + (2 * b + wt) * 32 + n;
             u32x4 pk;
-            int f;
             if (GATE_UP) {
-                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB), u1 = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB + 16);
-                pk = u32x4{pack_bf16x2(silu_mul_f(g0[0], u0[0]), silu_mul_f(g0[1], u0[1])),
-                           pack_bf16x2(silu_mul_f(g0[2], u0[2]), silu_mul_f(g0[3], u0[3])),
-                           pack_bf16x2(silu_mul_f(g1[0], u1[0]), silu_mul_f(g1[1], u1[1])),
-                           pack_bf16x2(silu_mul_f(g1[2], u1[2]), silu_mul_f(g1[3], u1[3]))};
-                f = wrow0 + ww * 64 + c * 8;
+                pk = u32x4{pack_bf16x2(silu_mul_f(v[p][0][0], v[p][2][0]), silu_mul_f(v[p][0][1], v[p][2][1])),
+                           pack_bf16x2(silu_mul_f(v[p][0][2], v[p][2][2]), silu_mul_f(v[p][0][3], v[p][2][3])),
+                           pack_bf16x2(silu_mul_f(v[p][1][0], v[p][3][0]), silu_mul_f(v[p][1][1], v[p][3][1])),
+                           pack_bf16x2(silu_mul_f(v[p][1][2], v[p][3][2]), silu_mul_f(v[p][1][3], v[p][3][3]))};
             } else {
-                pk = u32x4{pack_bf16x2(g0[0], g0[1]), pack_bf16x2(g0[2], g0[3]), pack_bf16x2(g1[0], g1[1]), pack_bf16x2(g1[2], g1[3])};
-                f = wrow0 + ww * 128 + c * 8;
+                pk = u32x4{pack_bf16x2(v[p][0][0], v[p][0][1]), pack_bf16x2(v[p][0][2], v[p][0][3]),
+                           pack_bf16x2(v[p][1][0], v[p][1][1]), pack_bf16x2(v[p][1][2], v[p][1][3])};
             }
-            if (row < row_end && f < NW) *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
+            if (row < row_end && f < NW) {
+                // the down pass streams out far more than the caches hold before it is read again
+                if (GATE_UP) *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
+                else __builtin_nontemporal_store(pk, reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f));
+            }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
@@ -295,22 +318,63 @@ bool big_gemm_applicable(const moe_shape_t &s) {
     // whole weight tiles in both passes, whole k tiles, and enough rows per expert to fill 256-row tiles
     return s.dtype == MOE_BF16 && s.H % big::BW == 0 && s.I % (big::BW / 2) == 0 && (long)s.T * s.K >= 128L * s.E;
 }
-int big_tile_rows() { return big::BT; }
+
+// ---- per-XCD row-tile list ---------------------------------------------------------------------------
+// list[x * tiles_per_xcd + i] = (expert, first row, end of the expert's rows, 0) of the i-th row tile of XCD x,
+// expert = -1 past the end.  One block: tile counts per expert, their prefix sum, then one entry per thread
+// and step, its expert found by bisection in the prefix sums.
+__global__ __launch_bounds__(1024) void build_xcd_tile_list_kernel(const int32_t *__restrict__ off, int E,
+                                                                   int tiles_per_xcd, i32x4 *__restrict__ list) {
+    __shared__ int first[kMaxExperts + 1];
+    for (int e = threadIdx.x; e < E; e += 1024) first[e] = (off[e + 1] - off[e] + big::BT - 1) / big::BT;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { const int v = first[e]; first[e] = run; run += v; }
+        first[E] = run;
+    }
+    __syncthreads();
+    const int n_tiles = first[E], q = (n_tiles + 7) >> 3;      // q <= tiles_per_xcd by the launcher's bound on n_tiles
+    for (int idx = threadIdx.x; idx < 8 * tiles_per_xcd; idx += 1024) {
+        const int x = idx / tiles_per_xcd, i = idx - x * tiles_per_xcd, t = x * q + i;
+        i32x4 entry = {-1, 0, 0, 0};
+        if (i < q && t < n_tiles) {
+            int lo = 0, hi = E;                                 // last e with first[e] <= t (experts without rows repeat a value)
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (first[mid] <= t) lo = mid; else hi = mid;
+            }
+            entry = i32x4{lo, off[lo] + (t - first[lo]) * big::BT, off[lo + 1], 0};
+        }
+        list[idx] = entry;
+    }
+}
+
+size_t big_tile_list_bytes(const moe_shape_t &s) {
+    const size_t max_tiles = (size_t)s.T * s.K / big::BT + s.E;
+    return 8 * ((max_tiles + 7) / 8) * sizeof(i32x4);
+}
 
 hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
                                      const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
-                                     bf16_t *act, const int32_t *tile_map, int max_tiles, bf16_t *y_perm,
-                                     hipStream_t st, Probe *probe) {
+                                     bf16_t *act, int32_t *tile_map, bf16_t *y_perm, hipStream_t st, Probe *probe) {
     using namespace big;
-    const int nw1 = (s.I + BW / 2 - 1) / (BW / 2), nw2 = (s.H + BW - 1) / BW;
-    const int g1 = ((max_tiles * nw1 + 7) / 8) * 8, g2 = ((max_tiles * nw2 + 7) / 8) * 8;
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<true>, dim3(g1), dim3(256), 0, st, x_rows, row_map, s.K, off, tile_map,
-                       max_tiles, wg, wu, act, s.H, s.I, nw1);
+    // every expert ends with at most one partial tile, so there are at most T*K/BT + E row tiles
+    const int max_tiles = s.T * s.K / BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    i32x4 *list = reinterpret_cast<i32x4 *>(tile_map);
+    hipLaunchKernelGGL(build_xcd_tile_list_kernel, dim3(1), dim3(1024), 0, st, off, s.E, tiles_per_xcd, list);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     probe_mark(probe);
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(g2), dim3(256), 0, st, (const bf16_t *)act,
-                       (const int32_t *)nullptr, 1, off, tile_map, max_tiles, wd, wd, y_perm, s.I, s.H, nw2);
+    const int nw1 = (s.I + BW / 2 - 1) / (BW / 2), nw2 = (s.H + BW - 1) / BW;
+    const int n_rows = s.T * s.K;
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<true>, dim3(8 * tiles_per_xcd * nw1), dim3(256), 0, st, x_rows, row_map,
+                       s.K, list, tiles_per_xcd, wg, wu, act, s.H, s.I, nw1, n_rows);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    probe_mark(probe);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(8 * tiles_per_xcd * nw2), dim3(256), 0, st, (const bf16_t *)act,
+                       (const int32_t *)nullptr, 1, list, tiles_per_xcd, wd, wd, y_perm, s.I, s.H, nw2, n_rows);
     return hipGetLastError();
 }
 

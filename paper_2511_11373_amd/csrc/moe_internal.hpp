@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) double f64x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int kWave = 64;
@@ -45,7 +46,7 @@ struct Workspace {
     int32_t *row_to_assign;  // [T*K]
     int32_t *assign_to_row;  // [T*K]
     int32_t *chunk_base;     // [nchunks, E] per-chunk histogram, then per-chunk first row
-    int32_t *tile_map;       // [2*max_tiles + 4]: tile -> (expert, first row), then tile count
+    int32_t *tile_map;       // row-tile list of the grouped GEMM (layout is the GEMM variant's own)
     bf16_t  *act;            // [T*K, I] bf16 activations silu(g)*u
     void    *y_perm;         // [T*K, H] dtype
     size_t   total;
