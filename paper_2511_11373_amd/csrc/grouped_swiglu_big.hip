@@ -96,11 +96,19 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
 
     // ---- which tile --------------------------------------------------------------------------
+    // Slot s of an XCD falls into row tile s / n_wtiles of that XCD's list; the entry there describes the run of
+    // consecutive row tiles of the same expert around it.  The run's blocks are walked weight tile fastest in
+    // the gate/up pass (neighbours share their token rows) and row tile fastest in the down pass (neighbours
+    // share their weights): measured, the passes differ by about a percent either way.
     const int slot = blockIdx.x >> 3;
-    const int wtile = slot % n_wtiles;
-    const i32x4 entry = tile_list[(blockIdx.x & 7) * tiles_per_xcd + slot / n_wtiles];
-    const int e = entry[0], row0 = entry[1], row_end = entry[2];
+    const i32x4 *entry = tile_list + 2 * ((blockIdx.x & 7) * tiles_per_xcd + slot / n_wtiles);
+    const i32x4 ea = entry[0], eb = entry[1];
+    const int e = ea[0], row_end = ea[2];
     if (e < 0) return;
+    const int in_run = slot - ea[3] * n_wtiles;                 // ea[3]: first row tile of the run in this XCD's list
+    const int wtile = GATE_UP ? in_run % n_wtiles : in_run / eb[0];      // eb[0]: row tiles in the run
+    const int rt = GATE_UP ? in_run / n_wtiles : in_run % eb[0];
+    const int row0 = ea[1] + (eb[1] + rt) * BT;                 // ea[1]: the expert's first row, eb[1]: the run's first tile in the expert
     const int wrow0 = wtile * (GATE_UP ? BW / 2 : BW);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -320,9 +328,12 @@ bool big_gemm_applicable(const moe_shape_t &s) {
 }
 
 // ---- per-XCD row-tile list ---------------------------------------------------------------------------
-// list[x * tiles_per_xcd + i] = (expert, first row, end of the expert's rows, 0) of the i-th row tile of XCD x,
-// expert = -1 past the end.  One block: tile counts per expert, their prefix sum, then one entry per thread
-// and step, its expert found by bisection in the prefix sums.
+// Two 16-byte words per row tile; XCD x owns row tiles [x*q, (x+1)*q) of the expert-ordered sequence, q = an
+// eighth of the tiles there are.  list[2*(x*tiles_per_xcd + i)] = (expert, first row of the expert, end of the
+// expert's rows, a) and the word after it (r, t0, 0, 0), where the expert's row tiles inside this XCD's share
+// are the r tiles starting at position a of the share, the first of them being tile t0 of the expert.
+// Expert = -1 past the end.  One block: tile counts per expert, their prefix sum, then one entry per thread and
+// step, its expert found by bisection in the prefix sums.
 __global__ __launch_bounds__(1024) void build_xcd_tile_list_kernel(const int32_t *__restrict__ off, int E,
                                                                    int tiles_per_xcd, i32x4 *__restrict__ list) {
     __shared__ int first[kMaxExperts + 1];
@@ -337,22 +348,26 @@ __global__ __launch_bounds__(1024) void build_xcd_tile_list_kernel(const int32_t
     const int n_tiles = first[E], q = (n_tiles + 7) >> 3;      // q <= tiles_per_xcd by the launcher's bound on n_tiles
     for (int idx = threadIdx.x; idx < 8 * tiles_per_xcd; idx += 1024) {
         const int x = idx / tiles_per_xcd, i = idx - x * tiles_per_xcd, t = x * q + i;
-        i32x4 entry = {-1, 0, 0, 0};
+        i32x4 ea = {-1, 0, 0, 0}, eb = {1, 0, 0, 0};
         if (i < q && t < n_tiles) {
             int lo = 0, hi = E;                                 // last e with first[e] <= t (experts without rows repeat a value)
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
                 if (first[mid] <= t) lo = mid; else hi = mid;
             }
-            entry = i32x4{lo, off[lo] + (t - first[lo]) * big::BT, off[lo + 1], 0};
+            const int share_end = min((x + 1) * q, n_tiles);
+            const int run_begin = max(first[lo], x * q), run_end = min(first[lo + 1], share_end);
+            ea = i32x4{lo, off[lo], off[lo + 1], run_begin - x * q};
+            eb = i32x4{run_end - run_begin, run_begin - first[lo], 0, 0};
         }
-        list[idx] = entry;
+        list[2 * idx] = ea;
+        list[2 * idx + 1] = eb;
     }
 }
 
 size_t big_tile_list_bytes(const moe_shape_t &s) {
     const size_t max_tiles = (size_t)s.T * s.K / big::BT + s.E;
-    return 8 * ((max_tiles + 7) / 8) * sizeof(i32x4);
+    return 2 * 8 * ((max_tiles + 7) / 8) * sizeof(i32x4);
 }
 
 hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
