@@ -31,7 +31,7 @@ Workspace carve_workspace(const moe_shape_t &s, void *base) {
     const size_t n = (size_t)s.T * s.K;
     const size_t nchunks = (n + kPermChunk - 1) / kPermChunk;
     const size_t max_tiles = n / kMinTokenTile + (size_t)s.E;
-    take(cur, w.logit_part, sizeof(double) * (size_t)router_ksplit(s) * s.T * s.E);
+    take(cur, w.logit_part, router_scratch_bytes(s));
     take(cur, w.topk_idx, sizeof(int32_t) * n);
     take(cur, w.topk_w, sizeof(float) * n);
     take(cur, w.expert_offsets, sizeof(int32_t) * ((size_t)s.E + 1));

@@ -58,6 +58,7 @@ constexpr int kMinTokenTile = 16;      // smallest row tile any GEMM variant use
 Workspace carve_workspace(const moe_shape_t &s, void *base);
 
 int router_ksplit(const moe_shape_t &s);
+size_t router_scratch_bytes(const moe_shape_t &s);
 
 // Optional stage timer: when given, launchers record an event at every stage boundary.
 struct Probe {

@@ -243,206 +243,276 @@ __global__ __launch_bounds__(256) void topk_rank_kernel(const double *__restrict
     write_weights(sel, K, renorm, denom_all, topk_w + (size_t)t * K, lane);
 }
 
-// ---- fast router (bf16 storage, renormalised weights, E <= 128, H <= 2048) -------------------------------------
+// ---- fast router (bf16 storage, renormalised weights, E <= 128, H <= 2048, many tokens) ------------------------
 // The selection must equal the one made on exactly summed logits, but only the logits near the top matter.
-// Step 1 gets every logit cheaply on the bf16 matrix cores (float accumulation) together with a rigorous error
-// radius; step 2 recomputes in double only the candidates that could be among the K largest, and ranks those.
+// Kernel 1 gets every logit cheaply on the bf16 matrix cores (float accumulation), with the squared norms of the
+// router rows that a rigorous error radius needs; kernel 2 recomputes in double only the candidates that could be
+// among the K largest, and ranks those.
 //
 // Error radius.  |fast - exact| <= kGamma * |x_t|_2 * |w_e|_2 + 4e-7 * (1 + |fast|): the fast logit is a sum of
-// H products (each exact in float) reduced by up to 8 chained 32-term MFMAs per k eighth, seven float adds and the
-// bias add.  Allowing each MFMA an error of 2^-21 of the magnitude it handles gives 2^-17 * sum|x_h w_h| in all;
-// Cauchy-Schwarz bounds that sum by the norms; kGamma = 2^-16 doubles it.
+// H <= 2048 products (each exact in float) accumulated by up to 64 chained 32-term MFMAs, plus the bias add.
+// Allowing each MFMA an error of 2^-21 of the magnitude it handles gives 2^-15 * sum|x_h w_h| in all;
+// Cauchy-Schwarz bounds that sum by the norms; kGamma = 2^-14 doubles it.
 // Candidates.  With lo_e = fast_e - r_e and hi_e = fast_e + r_e, the K-th largest lo is a lower bound tau of the
 // K-th largest exact logit, so every member of the exact top K (ties included) has hi_e >= tau.
-constexpr float kGamma = 1.52587890625e-05f;
+constexpr float kGamma = 6.103515625e-05f;
 
+// Butterfly partners inside a row of 16 lanes through the data-parallel-primitive lane permutations: lanes l^1 and
+// l^2 (quad permutations), then the mirror images inside 8 and 16 lanes, which pair every group of 4 (8) lanes
+// holding equal values with the other group of its half row (row).  The rows are paired by ordinary shuffles.
+template <int CTRL>
+__device__ __forceinline__ unsigned int dpp_u32(unsigned int v) {
+    return (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+__device__ __forceinline__ unsigned int wave_max_u32(unsigned int v) {
+    v = max(v, dpp_u32<kDppXor1>(v));
+    v = max(v, dpp_u32<kDppXor2>(v));
+    v = max(v, dpp_u32<kDppHalfMirror>(v));
+    v = max(v, dpp_u32<kDppMirror>(v));
+    v = max(v, (unsigned int)__shfl_xor((int)v, 16, 64));
+    v = max(v, (unsigned int)__shfl_xor((int)v, 32, 64));
+    return v;
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const unsigned long long o = (unsigned long long)dpp_u32<CTRL>((unsigned int)u) |
+                                 ((unsigned long long)dpp_u32<CTRL>((unsigned int)(u >> 32)) << 32);
+    return __builtin_bit_cast(double, o);
+}
 __device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    v += dpp_f64<kDppXor1>(v);
+    v += dpp_f64<kDppXor2>(v);
+    v += dpp_f64<kDppHalfMirror>(v);
+    v += dpp_f64<kDppMirror>(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
     return v;
 }
 
-// ranks[r] = number of (key, expert) pairs of this token that precede the lane's r-th expert; keys in LDS.
+// K-th largest of the wave's keys (lane l holds key[r] of expert l + 64 r; 0 = no expert), counting equal keys
+// as often as they occur: K rounds, each taking the maximum of what is left and striking out one holder of it.
 template <int R>
-__device__ __forceinline__ void rank_by_count(const unsigned int *keys, const unsigned int (&key)[R], int lane, int (&rank)[R]) {
+__device__ __forceinline__ unsigned int kth_largest_key(const unsigned int (&key)[R], int K, int lane) {
+    unsigned int taken = 0u, kth = 0u;
+    for (int k = 0; k < K; ++k) {
+        unsigned int best = 0u;
 #pragma unroll
-    for (int r = 0; r < R; ++r) rank[r] = 0;
-    for (int e4 = 0; e4 < R * 64; e4 += 4) {
-        const u32x4 k4 = *reinterpret_cast<const u32x4 *>(&keys[e4]);
+        for (int r = 0; r < R; ++r)
+            if (!((taken >> r) & 1u)) best = max(best, key[r]);
+        kth = wave_max_u32(best);
+        const unsigned long long holders = __ballot(best == kth);
+        if (lane == __ffsll((long long)holders) - 1) {
+            bool done = false;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int e = lane + 64 * r;
-                rank[r] += (k4[j] > key[r]) || (k4[j] == key[r] && (e4 + j) < e);
-            }
+            for (int r = 0; r < R; ++r)
+                if (!done && !((taken >> r) & 1u) && key[r] == kth) { taken |= 1u << r; done = true; }
+        }
     }
+    return kth;
 }
+
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Block = 16 tokens, 16 waves.  Step 1: wave w multiplies k eighth w%8 of expert tiles w/8, w/8+2, ...
-// (v_mfma_f32_16x16x32_bf16, experts as rows, tokens as columns).  Step 2: wave w owns token w.
+// Kernel 1: fast[t][e] for 64 tokens x EP = 64*R experts per block, k in steps of 128 through two LDS stages.
+// 8 waves: wave w owns expert tile w % (EP/16) and EP/32 of the four 16-token tiles (v_mfma_f32_16x16x32_bf16,
+// experts as rows, tokens as columns: lane (n, q) = (l%16, l/16) feeds row n, k = 8q..8q+7, and gets experts
+// 4q..4q+3 of token n).  LDS rows are 256 bytes; the 16-byte piece p of row r is stored at p ^ (r % 16) so that
+// the 16 rows read together at one k fall on different banks.
 template <int R>
-__global__ __launch_bounds__(1024) void router_fast_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wr,
-                                                           const float *__restrict__ bias, int32_t *__restrict__ topk_idx,
-                                                           float *__restrict__ topk_w, int T, int H, int E, int K) {
-    constexpr int EP = 64 * R;
-    __shared__ __attribute__((aligned(16))) float partial[8][16][EP];
-    __shared__ float wn2[8][EP];
-    __shared__ __attribute__((aligned(16))) unsigned int keys_all[16][EP];
-    __shared__ float sel_all[16][EP];
-    __shared__ int cid_all[16][EP];
-    __shared__ u32x4 xrow_all[16][256];          // the block's 16 token rows (H <= 2048), packed bf16
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int t0 = blockIdx.x * 16;
-    {
-        const int kq = wave & 7, tg = wave >> 3;
-        const int n = lane & 15, q = lane >> 4;
-        const int hq = H >> 3, steps = hq >> 5;            // H % 256 == 0, steps <= 8
-        const bf16_t *xp = x + (size_t)min(t0 + n, T - 1) * H + kq * hq + q * 8;
-        u32x4 xop[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) xop[s] = *reinterpret_cast<const u32x4 *>(xp + min(s, steps - 1) * 32);
-        const int ntiles = (E + 15) >> 4;
-        for (int et = tg; et < ntiles; et += 2) {
-            const bf16_t *wp = wr + (size_t)min(et * 16 + n, E - 1) * H + kq * hq + q * 8;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            float ss = 0.f;
-            u32x4 a[8];
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                a[s] = *reinterpret_cast<const u32x4 *>(wp + min(s, steps - 1) * 32);
-                if (s >= steps) a[s] = u32x4{0u, 0u, 0u, 0u};      // a zero weight piece contributes nothing
-            }
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[s]),
-                                                              __builtin_bit_cast(bf16x8, xop[s]), acc, 0, 0, 0);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float lo = __uint_as_float(a[s][j] << 16), hi = __uint_as_float(a[s][j] & 0xFFFF0000u);
-                    ss = fmaf(lo, lo, ss);
-                    ss = fmaf(hi, hi, ss);
-                }
-            }
-            // result register j of lane (n, q) is expert et*16 + 4q + j, token n
-            *reinterpret_cast<f32x4 *>(&partial[kq][n][et * 16 + 4 * q]) = acc;
-            ss += __shfl_xor(ss, 16, 64);
-            ss += __shfl_xor(ss, 32, 64);
-            if (q == 0) wn2[kq][et * 16 + n] = ss;
-        }
-    }
-    __syncthreads();
+__global__ __launch_bounds__(512) void router_fast_logits_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wr,
+                                                                 float *__restrict__ fast, float *__restrict__ wn2,
+                                                                 int T, int H, int E) {
+    constexpr int EP = 64 * R, NT = EP / 16, TPW = NT / 2;      // expert tiles, token tiles per wave
+    constexpr int BK = 128, ROWB = BK * 2, WP = EP * 16 / 512, XP = 64 * 16 / 512;   // pieces per thread and stage
+    __shared__ __attribute__((aligned(16))) unsigned char Ws[2][EP * ROWB];
+    __shared__ __attribute__((aligned(16))) unsigned char Xs[2][64 * ROWB];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, q = lane >> 4;
+    const int et = wave % NT, th = wave / NT;
+    const int t0 = blockIdx.x * 64;
 
-    const int t = t0 + wave;
+    // global sources and LDS targets of this thread's pieces (rows past the end are clamped: their results are unused)
+    const bf16_t *wsrc[WP], *xsrc[XP];
+    int wdst[WP], xdst[XP];
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+        const int g = tid + i * 512, r = g >> 4, pc = g & 15;
+        wsrc[i] = wr + (size_t)min(r, E - 1) * H + pc * 8;
+        wdst[i] = r * ROWB + ((pc ^ (r & 15)) << 4);
+    }
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+        const int g = tid + i * 512, r = g >> 4, pc = g & 15;
+        xsrc[i] = x + (size_t)min(t0 + r, T - 1) * H + pc * 8;
+        xdst[i] = r * ROWB + ((pc ^ (r & 15)) << 4);
+    }
+    u32x4 wreg[WP], xreg[XP];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < WP; ++i) wreg[i] = *reinterpret_cast<const u32x4 *>(wsrc[i] + k0);
+#pragma unroll
+        for (int i = 0; i < XP; ++i) xreg[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + k0);
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < WP; ++i) *reinterpret_cast<u32x4 *>(&Ws[buf][wdst[i]]) = wreg[i];
+#pragma unroll
+        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(&Xs[buf][xdst[i]]) = xreg[i];
+    };
+
+    f32x4 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float ss = 0.f;
+    const int nk = H / BK;          // H is a multiple of 256
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) fetch((kt + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 32; ++ks) {
+            const int pc = ((ks * 4 + q) ^ n) << 4;
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(&Ws[buf][(et * 16 + n) * ROWB + pc]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float lo = __uint_as_float(a[j] << 16), hi = __uint_as_float(a[j] & 0xFFFF0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
+            }
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const u32x4 b = *reinterpret_cast<const u32x4 *>(&Xs[buf][((th * TPW + i) * 16 + n) * ROWB + pc]);
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                                 acc[i], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < nk) stash(buf ^ 1);      // the other stage was last read before the previous barrier
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int t = t0 + (th * TPW + i) * 16 + n;
+        if (t < T) *reinterpret_cast<f32x4 *>(fast + (size_t)t * EP + et * 16 + 4 * q) = acc[i];
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (blockIdx.x == 0 && th == 0 && q == 0) wn2[et * 16 + n] = ss;
+}
+
+// Kernel 2: one wave per token.  Lane l keeps the token's values 8*(l + 64 j) .. +7 as doubles, so a candidate's
+// exact logit costs one load, one widening and one fused multiply-add per element and a wave-wide sum.
+template <int R>
+__global__ __launch_bounds__(256) void router_fast_select_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wr,
+                                                                 const float *__restrict__ bias, const float *__restrict__ fast,
+                                                                 const float *__restrict__ wn2, int32_t *__restrict__ topk_idx,
+                                                                 float *__restrict__ topk_w, int T, int H, int E, int K) {
+    constexpr int EP = 64 * R;
+    __shared__ __attribute__((aligned(16))) unsigned int keys_all[4][EP];
+    __shared__ float sel_all[4][EP];
+    __shared__ int cid_all[4][EP];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + wave;
     if (t >= T) return;
-    unsigned int *ckey = keys_all[wave];     // candidate list: ordered exact-logit bits ...
-    int *cid = cid_all[wave];                // ... and expert ids
+    unsigned int *ckey = keys_all[wave];     // the candidates' exact-logit bits
+    int *cid = cid_all[wave];                // candidate expert ids
     float *sel = sel_all[wave];              // selected logits by slot
-    // The wave works as 4 groups of 16 lanes so that four candidates are re-evaluated at a time; the token row
-    // sits in LDS (piece p = 8 values) and lane li of a group handles pieces li, li+16, ...
-    const int grp = lane >> 4, li = lane & 15;
-    const int npp = H >> 7;                  // pieces per lane: H/8/16 <= 16
-    u32x4 *xrow = xrow_all[wave];
+
+    // the token row: pieces lane, lane+64, ... of 8 values (H <= 2048: at most 4 per lane), widened once
+    const int npieces = H >> 3;
+    double xd[4][8];
     float xsq = 0.f;
-    for (int p = lane; p < (H >> 3); p += 64) {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)t * H + p * 8);
-        xrow[p] = v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int pc = lane + 64 * j;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (pc < npieces) v = *reinterpret_cast<const u32x4 *>(x + (size_t)t * H + pc * 8);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xFFFF0000u);
             xsq = fmaf(lo, lo, xsq);
             xsq = fmaf(hi, hi, xsq);
+            xd[j][2 * i] = (double)lo;
+            xd[j][2 * i + 1] = (double)hi;
         }
     }
     const float xnorm = sqrtf(wave_sum_f32(xsq)) * 1.0001f;
 
-    float fast[R], rad[R];
+    float fst[R], rad[R];
     unsigned int lokey[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
         float f = 0.f, w2 = 0.f;
         if (e < E) {
-#pragma unroll
-            for (int z = 0; z < 8; ++z) { f += partial[z][wave][e]; w2 += wn2[z][e]; }
+            f = fast[(size_t)t * EP + e];
+            w2 = wn2[e];
             if (bias) f += bias[e];
         }
-        fast[r] = f;
+        fst[r] = f;
         rad[r] = kGamma * xnorm * (sqrtf(w2) * 1.0001f) + 4e-7f * (1.0f + fabsf(f));
         lokey[r] = e < E ? float_order_bits(f - rad[r]) : 0u;       // 0 sorts below every finite float
     }
-    // tau = K-th largest lower bound, by radix selection on the ordered bits (ballots only)
-    unsigned int prefix = 0u;
-    int remaining = K;
-    for (int bit = 31; bit >= 0; --bit) {
-        const unsigned int want = prefix | (1u << bit), mask = ~((1u << bit) - 1u);
-        int cnt = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) cnt += __popcll(__ballot((lokey[r] & mask) == want));
-        if (cnt >= remaining) prefix = want; else remaining -= cnt;
-    }
-    const float tau = order_bits_float(prefix);
+    const float tau = order_bits_float(kth_largest_key<R>(lokey, K, lane));     // K <= E: a real expert's bound
 
     // candidate list, in expert order
     int nc = 0;
     const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const bool cand = lane + 64 * r < E && fast[r] + rad[r] >= tau;
+        const bool cand = lane + 64 * r < E && fst[r] + rad[r] >= tau;
         const unsigned long long m = __ballot(cand);
         if (cand) cid[nc + __popcll(m & below)] = lane + 64 * r;
         nc += __popcll(m);
     }
     wave_lds_sync();
-    // exact logits of the candidates, four at a time: the sum in double (products exact), one rounding to float
-    for (int c0 = 0; c0 < nc; c0 += 4) {
-        const int ci = c0 + grp;
-        const int e = cid[ci < nc ? ci : c0];
-        const bf16_t *wrow = wr + (size_t)e * H + li * 8;
-        double s = 0.0;
+    // exact logits of the candidates: the sum in double (products exact), one rounding to float
+    u32x4 wv[4];
+    auto fetch_row = [&](int e) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            u32x4 wv[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (half * 8 + j < npp) v = *reinterpret_cast<const u32x4 *>(wrow + (half * 8 + j) * 128);
-                wv[j] = v;
-            }
-            u32x4 xv4[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) xv4[j] = xrow[li + 16 * min(half * 8 + j, npp - 1)];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const unsigned int xv = xv4[j][i], ww = wv[j][i];
-                    s = fma((double)__uint_as_float(xv << 16), (double)__uint_as_float(ww << 16), s);
-                    s = fma((double)__uint_as_float(xv & 0xFFFF0000u), (double)__uint_as_float(ww & 0xFFFF0000u), s);
-                }
-                __builtin_amdgcn_sched_barrier(0);      // keeps the widening to double from being hoisted (registers)
-            }
+        for (int j = 0; j < 4; ++j) {
+            const int pc = lane + 64 * j;
+            wv[j] = u32x4{0u, 0u, 0u, 0u};
+            if (pc < npieces) wv[j] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e * H + pc * 8);
         }
+    };
+    fetch_row(cid[0]);                                   // K >= 1, so there is at least one candidate
+    for (int ci = 0; ci < nc; ++ci) {
+        const int e = cid[ci];
+        u32x4 cur[4];
 #pragma unroll
-        for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
+        for (int j = 0; j < 4; ++j) cur[j] = wv[j];
+        if (ci + 1 < nc) fetch_row(cid[ci + 1]);         // the next row travels while this one is summed
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                s0 = fma(xd[j][2 * i], (double)__uint_as_float(cur[j][i] << 16), s0);
+                s1 = fma(xd[j][2 * i + 1], (double)__uint_as_float(cur[j][i] & 0xFFFF0000u), s1);
+            }
+        double s = wave_sum_f64(s0 + s1);
         if (bias) s += (double)bias[e];
-        if (li == 0 && ci < nc) ckey[ci] = float_order_bits((float)s);
+        if (lane == 0) ckey[ci] = float_order_bits((float)s);
     }
     wave_lds_sync();
     // order the candidates: (exact logit descending, expert id ascending); the first K are the selection
     for (int ci = lane; ci < nc; ci += 64) {
         const unsigned int mykey = ckey[ci];
         const int myid = cid[ci];
-        int rank = 0;
-        for (int cj = 0; cj < nc; ++cj) rank += (ckey[cj] > mykey) || (ckey[cj] == mykey && cid[cj] < myid);
-        if (rank < K) {
-            topk_idx[(size_t)t * K + rank] = myid;
-            sel[rank] = order_bits_float(mykey);
+        int rk = 0;
+        for (int cj = 0; cj < nc; ++cj) rk += (ckey[cj] > mykey) || (ckey[cj] == mykey && cid[cj] < myid);
+        if (rk < K) {
+            topk_idx[(size_t)t * K + rk] = myid;
+            sel[rk] = order_bits_float(mykey);
         }
     }
     wave_lds_sync();
@@ -465,14 +535,27 @@ int router_ksplit(const moe_shape_t &s) {
     return (nchunks + cps - 1) / cps;
 }
 
+// Bytes of scratch launch_route needs: the k-split partial sums in double, or the fast path's float logits and norms.
+size_t router_scratch_bytes(const moe_shape_t &s) {
+    const size_t part = sizeof(double) * (size_t)router_ksplit(s) * s.T * s.E;
+    const size_t fast = router_fast_applicable(s) ? sizeof(float) * ((size_t)s.T + 1) * 128 : 0;
+    return part > fast ? part : fast;
+}
+
 hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_router, const float *bias,
                         double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st, Probe *probe) {
     if (router_fast_applicable(s)) {
-        dim3 grid((s.T + 15) / 16);
         const bf16_t *xb = (const bf16_t *)x, *wb = (const bf16_t *)w_router;
-        if (s.E <= 64) hipLaunchKernelGGL(router_fast_kernel<1>, grid, dim3(1024), 0, st, xb, wb, bias, topk_idx, topk_w, s.T, s.H, s.E, s.K);
-        else hipLaunchKernelGGL(router_fast_kernel<2>, grid, dim3(1024), 0, st, xb, wb, bias, topk_idx, topk_w, s.T, s.H, s.E, s.K);
+        const int ep = s.E <= 64 ? 64 : 128;
+        float *fast = reinterpret_cast<float *>(logit_part), *wn2 = fast + (size_t)s.T * ep;
+        dim3 g1((s.T + 63) / 64), g2((s.T + 3) / 4);
+        if (ep == 64) hipLaunchKernelGGL(router_fast_logits_kernel<1>, g1, dim3(512), 0, st, xb, wb, fast, wn2, s.T, s.H, s.E);
+        else hipLaunchKernelGGL(router_fast_logits_kernel<2>, g1, dim3(512), 0, st, xb, wb, fast, wn2, s.T, s.H, s.E);
+        hipError_t e1 = hipGetLastError();
+        if (e1 != hipSuccess) return e1;
         probe_mark(probe);
+        if (ep == 64) hipLaunchKernelGGL(router_fast_select_kernel<1>, g2, dim3(256), 0, st, xb, wb, bias, fast, wn2, topk_idx, topk_w, s.T, s.H, s.E, s.K);
+        else hipLaunchKernelGGL(router_fast_select_kernel<2>, g2, dim3(256), 0, st, xb, wb, bias, fast, wn2, topk_idx, topk_w, s.T, s.H, s.E, s.K);
         return hipGetLastError();
     }
     const int ks = router_ksplit(s);
