@@ -353,31 +353,26 @@ __global__ __launch_bounds__(512) void router_fast_logits_kernel(const bf16_t *_
         xsrc[i] = x + (size_t)min(t0 + r, T - 1) * H + pc * 8;
         xdst[i] = r * ROWB + ((pc ^ (r & 15)) << 4);
     }
-    u32x4 wreg[WP], xreg[XP];
-    auto fetch = [&](int k0) {
+    // two register sets: the k tiles of the next two stages are in flight while one is multiplied
+    u32x4 wreg[2][WP], xreg[2][XP];
+    auto fetch = [&](int set, int k0) {
 #pragma unroll
-        for (int i = 0; i < WP; ++i) wreg[i] = *reinterpret_cast<const u32x4 *>(wsrc[i] + k0);
+        for (int i = 0; i < WP; ++i) wreg[set][i] = *reinterpret_cast<const u32x4 *>(wsrc[i] + k0);
 #pragma unroll
-        for (int i = 0; i < XP; ++i) xreg[i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + k0);
+        for (int i = 0; i < XP; ++i) xreg[set][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + k0);
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int set, int buf) {
 #pragma unroll
-        for (int i = 0; i < WP; ++i) *reinterpret_cast<u32x4 *>(&Ws[buf][wdst[i]]) = wreg[i];
+        for (int i = 0; i < WP; ++i) *reinterpret_cast<u32x4 *>(&Ws[buf][wdst[i]]) = wreg[set][i];
 #pragma unroll
-        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(&Xs[buf][xdst[i]]) = xreg[i];
+        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(&Xs[buf][xdst[i]]) = xreg[set][i];
     };
 
     f32x4 acc[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     float ss = 0.f;
-    const int nk = H / BK;          // H is a multiple of 256
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) fetch((kt + 1) * BK);
+    auto multiply = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < BK / 32; ++ks) {
             const int pc = ((ks * 4 + q) ^ n) << 4;
@@ -395,7 +390,20 @@ __global__ __launch_bounds__(512) void router_fast_logits_kernel(const bf16_t *_
                                                                  acc[i], 0, 0, 0);
             }
         }
-        if (kt + 1 < nk) stash(buf ^ 1);      // the other stage was last read before the previous barrier
+    };
+    const int nk = H / BK;          // H is a multiple of 256: an even number of stages, two per turn of the loop
+    fetch(0, 0);
+    fetch(1, BK);
+    stash(0, 0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+        if (kt + 2 < nk) fetch(0, (kt + 2) * BK);
+        multiply(0);
+        stash(1, 1);                              // stage kt+1; buffer 1 was last read before the previous barrier
+        __syncthreads();
+        if (kt + 3 < nk) fetch(1, (kt + 3) * BK);
+        multiply(1);
+        if (kt + 2 < nk) stash(0, 0);
         __syncthreads();
     }
 #pragma unroll

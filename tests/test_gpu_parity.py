@@ -120,7 +120,8 @@ def test_near_ties_go_through_the_exact_recheck(lib, oracle_lib):
     """Router rows that differ from each other by one bf16 ulp in a few places, and exact duplicates: the
     logits of such experts differ by far less than float accumulation error, so only an exact re-evaluation
     can order them.  Shapes on both the matrix-core fast path (T >= 1024, H % 256 == 0, E <= 128) and the fp64 path."""
-    for (T, H, E, K, seed) in ((1100, 512, 96, 8, 21), (1025, 2048, 128, 8, 22), (300, 512, 96, 8, 24), (64, 384, 40, 6, 23)):
+    for (T, H, E, K, seed) in ((1100, 512, 96, 8, 21), (1025, 2048, 128, 8, 22), (300, 512, 96, 8, 24), (64, 384, 40, 6, 23),
+                               (1030, 1792, 64, 8, 25), (1200, 768, 33, 33, 26), (1027, 256, 5, 1, 27)):
         cfg = wl.small_config(T, H, E, K, 64, dtype=wl.BF16, seed=seed, sigma_w=0.02)
         d = wl.make_inputs(cfg)
         wr = d["w_router"].copy()
@@ -140,6 +141,23 @@ def test_near_ties_go_through_the_exact_recheck(lib, oracle_lib):
         o_idx, o_w = oracle_lib.route_topk(d["x_f32"], wl.bf16_bits_to_f32(wr), K, bias)
         assert np.array_equal(host(idx), o_idx), (T, H, E)
         check_weights(host(w), o_w)
+
+
+def test_grouped_gemm_uneven_experts(lib, oracle_lib):
+    """The large-batch GEMM on hand-made expert segments: experts without rows at the start, in the middle and at
+    the end, segments of 1, 3, 256 and 257 rows, and one expert that holds most of the rows and therefore spans
+    several of the per-XCD shares of the row-tile list."""
+    counts = [0, 700, 0, 257, 256, 1, 0, 2500, 3, 0, 512, 0]
+    n, H, I, E = sum(counts), 256, 128, len(counts)
+    cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=31, sigma_w=0.05)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    y = moe.moe_grouped_swiglu(shp, g["x"], torch.from_numpy(off).cuda(), g["w_gate"], g["w_up"], g["w_down"], ws)
+    o_y = oracle_lib.grouped_swiglu(d["x_f32"], off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
+    check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
 
 
 def test_empty_batch_and_bad_arguments(lib):
