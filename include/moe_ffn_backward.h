@@ -1,0 +1,66 @@
+/*
+ * moe_ffn_backward.h - C ABI of the backward pass of the routed-expert MoE FFN block declared in
+ * moe_ffn.h, for AMD gfx950 (MI355X), one GPU.
+ *
+ * The trainer maximises the objective of Section 2.2 (Eq. 2-3) with AdamW (Section 4.1, "Training
+ * Details"), which differentiates every layer of the policy, this block included.  The paper does not spell
+ * the gradient out; what is implemented is the chain rule through the operation moe_ffn.h defines, with
+ * the top-K selection held fixed (it is piecewise constant and carries no gradient):
+ *
+ *   out_t = sum_k w_k y_k               dw_k  = <d_out_t, y_k>
+ *   w = softmax(l over the selection)   dl_k  = w_k (dw_k - sum_j w_j dw_j)
+ *   l_e = <x_t, Wr_e> + b_e             dx_t += sum_k dl_k Wr_e;  dWr_e += dl x_t;  db_e += dl
+ *   y = Wd a, a = silu(g) u             da = w_k Wd^T d_out_t;  dWd_e += (w_k d_out_t) a^T
+ *   g = Wg x, u = Wu x                  dg = da u silu'(g), du = da silu(g), silu'(g) = s (1 + g (1 - s)), s = 1/(1+e^-g)
+ *                                       dWg_e += dg x_t^T;  dWu_e += du x_t^T;  dx_t += Wg^T dg + Wu^T du
+ *
+ * Conventions: those of moe_ffn.h (device pointers unless marked host, dense row-major tensors, caller-owned
+ * buffers and stream, nothing allocated or kept, arguments validated on the host before anything is enqueued,
+ * every data pointer 16-byte aligned, outputs overwritten in full, T == 0 gives zero weight gradients).
+ * Restrictions of this pass: shape->dtype must be MOE_BF16 (else MOE_ERR_DTYPE) and shape->renormalize must be
+ * nonzero (else MOE_ERR_SHAPE).  x, the weights, d_out, d_x and the row gradients are bf16; every weight
+ * gradient is float and is written, not accumulated into (an expert that received no row gets zeros).
+ * Nothing is kept from a forward call: routing, permutation and the expert pre-activations are recomputed.
+ * Intermediates are rounded to bf16, sums run in float on the matrix cores.
+ */
+#ifndef MOE_FFN_BACKWARD_H
+#define MOE_FFN_BACKWARD_H
+
+#include "moe_ffn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Host only.  Bytes of scratch that the two entry points below need for `shape`; a multiple of 256. */
+moe_status_t moe_backward_workspace_bytes(const moe_shape_t *shape, size_t *out_bytes);
+
+/*
+ * Backward of moe_grouped_swiglu over expert-sorted rows (the data- and weight-gradient grouped GEMMs).
+ *   x_perm   [T*K,H] bf16     expert_offsets [E+1] int32     w_gate, w_up [E,I,H] bf16     w_down [E,H,I] bf16
+ *   dy_perm  [T*K,H] bf16: dL/dy for every row
+ *   d_x_perm [T*K,H] bf16 out       d_w_gate, d_w_up [E,I,H] float out       d_w_down [E,H,I] float out
+ */
+moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x_perm, const int32_t *expert_offsets,
+                                         const void *w_gate, const void *w_up, const void *w_down, const void *dy_perm,
+                                         void *d_x_perm, float *d_w_gate, float *d_w_up, float *d_w_down,
+                                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Backward of moe_forward: all gradients of <out, d_out> in one call.
+ *   x [T,H], w_router [E,H], w_gate, w_up [E,I,H], w_down [E,H,I]: bf16; router_bias [E] float or NULL
+ *   d_out [T,H] bf16
+ *   d_x [T,H] bf16 out      d_w_router [E,H] float out      d_router_bias [E] float out or NULL
+ *   d_w_gate, d_w_up [E,I,H] float out      d_w_down [E,H,I] float out
+ * Sums over the rows of an expert run in row order and sums over a token's K slots in slot order, so two calls
+ * on the same inputs give the same bits.
+ */
+moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                          const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                          void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                          float *d_w_down, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_FFN_BACKWARD_H */

@@ -1,0 +1,319 @@
+// Backward pass of the MoE FFN block (bf16 storage, renormalised routing weights): entry points, the row-wise
+// kernels around the grouped GEMMs of backward_gemm.hip, and the workspace.
+//
+// With the selection S_t held fixed (it is piecewise constant), for d_out = dL/d_out:
+//   out_t = sum_k w_k y_k            dw_k = <d_out_t, y_k> = <d_out_t Wd, a_k>      (no need to rebuild y)
+//   w = softmax(l[S_t])              dl_k = w_k (dw_k - sum_j w_j dw_j)
+//   l_e = <x_t, Wr_e> + b_e          dx_t += sum_k dl_k Wr_e,  dWr_e += dl x_t,  db_e += dl
+//   y = Wd a, a = silu(g) u          da = w_k (d_out_t Wd),  dWd_e += d_out_t (x) (w_k a)
+//   g = Wg x, u = Wu x               dg = da u silu'(g),  du = da silu(g),  silu'(g) = s (1 + g (1 - s)),  s = 1/(1+e^-g)
+//                                    dWg_e += dg (x) x_t,  dWu_e += du (x) x_t,  dx_t += dg Wg + du Wu
+// g, u are recomputed from x (nothing is kept from a forward call).  Intermediates are bf16, sums are float.
+#include <type_traits>
+
+#include "moe_internal.hpp"
+
+#include "moe_ffn_backward.h"
+
+namespace moe {
+
+hipError_t launch_bw_rows_kfast(const bf16_t *rows, const int32_t *row_map, int row_div, const bf16_t *w, const int32_t *off,
+                                const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st);
+hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const int32_t *row_map, int row_div, const bf16_t *w0,
+                                const bf16_t *w1, const int32_t *off, const int32_t *tile_map, int max_tiles, bf16_t *out,
+                                int KD, int N, hipStream_t st);
+hipError_t launch_bw_wgrad(const bf16_t *P, const int32_t *p_map, int p_div, const bf16_t *Q, const int32_t *q_map, int q_div,
+                           const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
+hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
+
+namespace {
+
+constexpr int kBwTile = 256;       // row tile of the backward GEMMs
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// One wave per expert-sorted row r: from g, u and dq = d_out_t Wd (all [n][I] bf16) and the row's routing weight w,
+//   a = silu(g) u,  dw_row[r] = <dq, a>,  da = w dq,  dg = da u silu'(g),  du = da silu(g),  aw = w a.
+__global__ __launch_bounds__(256) void bw_swiglu_kernel(const bf16_t *__restrict__ g, const bf16_t *__restrict__ u,
+                                                        const bf16_t *__restrict__ dq, const float *__restrict__ topk_w,
+                                                        const int32_t *__restrict__ row_to_assign, bf16_t *__restrict__ dg,
+                                                        bf16_t *__restrict__ du, bf16_t *__restrict__ aw,
+                                                        float *__restrict__ dw_row, int n, int I) {
+    const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n) return;
+    const float w = topk_w ? topk_w[row_to_assign ? row_to_assign[r] : r] : 1.0f;
+    float dot = 0.f;
+    for (int p = lane; p < (I >> 3); p += 64) {
+        const size_t at = (size_t)r * I + p * 8;
+        const u32x4 gv = *reinterpret_cast<const u32x4 *>(g + at), uv = *reinterpret_cast<const u32x4 *>(u + at),
+                    qv = *reinterpret_cast<const u32x4 *>(dq + at);
+        float odg[8], odu[8], oaw[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float gf = __uint_as_float((j & 1) ? (gv[j >> 1] & 0xFFFF0000u) : (gv[j >> 1] << 16));
+            const float uf = __uint_as_float((j & 1) ? (uv[j >> 1] & 0xFFFF0000u) : (uv[j >> 1] << 16));
+            const float qf = __uint_as_float((j & 1) ? (qv[j >> 1] & 0xFFFF0000u) : (qv[j >> 1] << 16));
+            const float s = 1.0f / (1.0f + __expf(-gf));
+            const float a = gf * s * uf;
+            dot = fmaf(qf, a, dot);
+            const float da = w * qf;
+            odg[j] = da * uf * (s * (1.0f + gf * (1.0f - s)));
+            odu[j] = da * (gf * s);
+            oaw[j] = w * a;
+        }
+        *reinterpret_cast<u32x4 *>(dg + at) = u32x4{pack_bf16x2(odg[0], odg[1]), pack_bf16x2(odg[2], odg[3]), pack_bf16x2(odg[4], odg[5]), pack_bf16x2(odg[6], odg[7])};
+        *reinterpret_cast<u32x4 *>(du + at) = u32x4{pack_bf16x2(odu[0], odu[1]), pack_bf16x2(odu[2], odu[3]), pack_bf16x2(odu[4], odu[5]), pack_bf16x2(odu[6], odu[7])};
+        *reinterpret_cast<u32x4 *>(aw + at) = u32x4{pack_bf16x2(oaw[0], oaw[1]), pack_bf16x2(oaw[2], oaw[3]), pack_bf16x2(oaw[4], oaw[5]), pack_bf16x2(oaw[6], oaw[7])};
+    }
+    dot = wave_sum(dot);
+    if (lane == 0 && dw_row) dw_row[r] = dot;
+}
+
+// One thread per token: dl_k = w_k (dw_k - sum_j w_j dw_j), written per assignment.
+__global__ __launch_bounds__(256) void bw_softmax_kernel(const float *__restrict__ topk_w, const float *__restrict__ dw_row,
+                                                         const int32_t *__restrict__ assign_to_row, float *__restrict__ dl,
+                                                         int T, int K) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    float mean = 0.f;
+    for (int k = 0; k < K; ++k) mean = fmaf(topk_w[(size_t)t * K + k], dw_row[assign_to_row[(size_t)t * K + k]], mean);
+    for (int k = 0; k < K; ++k) {
+        const size_t a = (size_t)t * K + k;
+        dl[a] = topk_w[a] * (dw_row[assign_to_row[a]] - mean);
+    }
+}
+
+// One block per token: dx_t = sum_k dxp[row(t,k)] + sum_k dl_k Wr[e_k], float sums in k order, rounded once.
+__global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ dxp, const int32_t *__restrict__ assign_to_row,
+                                                    const float *__restrict__ dl, const int32_t *__restrict__ topk_idx,
+                                                    const bf16_t *__restrict__ wr, bf16_t *__restrict__ dx, int H, int K) {
+    const int t = blockIdx.x;
+    for (int p = threadIdx.x; p < (H >> 3); p += 256) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int k = 0; k < K; ++k) {
+            const size_t a = (size_t)t * K + k;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(dxp + (size_t)assign_to_row[a] * H + p * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[2 * j] += __uint_as_float(v[j] << 16);
+                acc[2 * j + 1] += __uint_as_float(v[j] & 0xFFFF0000u);
+            }
+        }
+        for (int k = 0; k < K; ++k) {
+            const size_t a = (size_t)t * K + k;
+            const float c = dl[a];
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(wr + (size_t)topk_idx[a] * H + p * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[2 * j] = fmaf(c, __uint_as_float(v[j] << 16), acc[2 * j]);
+                acc[2 * j + 1] = fmaf(c, __uint_as_float(v[j] & 0xFFFF0000u), acc[2 * j + 1]);
+            }
+        }
+        *reinterpret_cast<u32x4 *>(dx + (size_t)t * H + p * 8) =
+            u32x4{pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7])};
+    }
+}
+
+// Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl[a(r)] x[t(r)][h], in row order (the rows of
+// an expert are in increasing assignment order, so the sum is reproducible); block (e, 512-wide slice of h), one wave.
+__global__ __launch_bounds__(64) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x, const float *__restrict__ dl,
+                                                             const int32_t *__restrict__ row_to_assign, const int32_t *__restrict__ off,
+                                                             float *__restrict__ dwr, float *__restrict__ dbias, int H, int K) {
+    const int e = blockIdx.x, h0 = blockIdx.y * 512 + threadIdx.x * 8;
+    const int r0 = off[e], r1 = off[e + 1];
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    float bsum = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const int a = row_to_assign[r];
+        const float c = dl[a];
+        bsum += c;
+        if (h0 < H) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)(a / K) * H + h0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[2 * j] = fmaf(c, __uint_as_float(v[j] << 16), acc[2 * j]);
+                acc[2 * j + 1] = fmaf(c, __uint_as_float(v[j] & 0xFFFF0000u), acc[2 * j + 1]);
+            }
+        }
+    }
+    if (h0 < H) {
+        *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+        *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0 + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+    }
+    if (dbias && blockIdx.y == 0 && threadIdx.x == 0) dbias[e] = bsum;
+}
+
+__global__ __launch_bounds__(256) void bw_zero_kernel(float *__restrict__ p, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+// zero-fill by a kernel (safe to record into a HIP graph)
+hipError_t zero_floats(float *p, size_t count, hipStream_t st) {
+    if (!p || count == 0) return hipSuccess;
+    const size_t blocks = (count + 255) / 256;
+    hipLaunchKernelGGL(bw_zero_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, p, count);
+    return hipGetLastError();
+}
+
+struct BwWorkspace {
+    Workspace fwd;          // routing, permutation, tile list; fwd.act holds g, fwd.y_perm holds the row gradients dxp
+    bf16_t *u, *dq, *dg, *du, *aw;      // [n][I] each
+    float *dw_row, *dl;                 // [n] each
+    size_t total;
+};
+
+BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
+    BwWorkspace b;
+    b.fwd = carve_workspace(s, base);
+    char *cur = reinterpret_cast<char *>(base) + b.fwd.total;
+    const size_t n = (size_t)s.T * s.K;
+    auto take = [&](auto *&field, size_t bytes) {
+        field = reinterpret_cast<std::remove_reference_t<decltype(field)>>(cur);
+        cur += align256(bytes);
+    };
+    take(b.u, n * s.I * 2);
+    take(b.dq, n * s.I * 2);
+    take(b.dg, n * s.I * 2);
+    take(b.du, n * s.I * 2);
+    take(b.aw, n * s.I * 2);
+    take(b.dw_row, n * 4);
+    take(b.dl, n * 4);
+    b.total = (size_t)(cur - reinterpret_cast<char *>(base));
+    return b;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+moe_status_t check_bw_shape(const moe_shape_t *s) {
+    if (!s) return MOE_ERR_NULL;
+    if (s->T < 0 || s->H < 1 || s->E < 1 || s->K < 1 || s->I < 1 || s->K > s->E || s->E > kMaxExperts) return MOE_ERR_SHAPE;
+    if ((s->H & 7) || (s->I & 7)) return MOE_ERR_SHAPE;
+    if ((long long)s->T * s->K > 0x7FFFFFFFLL || (long long)s->T * s->E > 0x7FFFFFFFLL) return MOE_ERR_SHAPE;
+    if (s->dtype != MOE_BF16) return MOE_ERR_DTYPE;          // the backward pass is written for bf16 storage
+    if (!s->renormalize) return MOE_ERR_SHAPE;               // ... and for weights renormalised over the selection
+    return MOE_OK;
+}
+
+// The expert part: rows are x (gathered through row_map / K) or x_perm; up = d_out (gathered) or dy_perm.
+hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_map,
+                           const float *topk_w, const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
+                           BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu, float *d_wd, hipStream_t st) {
+    const int n = s.T * s.K, H = s.H, I = s.I, E = s.E;
+    const int max_tiles = n / kBwTile + (E < n ? E : n);
+    int32_t *tiles = b.fwd.tile_map;
+    bf16_t *g = b.fwd.act;
+    hipError_t err;
+#define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
+    MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
+    MOE_TRY(launch_bw_rows_kfast(x_rows, row_map, s.K, wg, off, tiles, max_tiles, g, H, I, st));
+    MOE_TRY(launch_bw_rows_kfast(x_rows, row_map, s.K, wu, off, tiles, max_tiles, b.u, H, I, st));
+    MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, row_map, s.K, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
+    hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_map, b.dg, b.du, b.aw,
+                       b.dw_row, n, I);
+    MOE_TRY(hipGetLastError());
+    MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, nullptr, 1, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
+    MOE_TRY(launch_bw_wgrad(up_rows, row_map, s.K, b.aw, nullptr, 1, off, E, d_wd, H, I, st));
+    MOE_TRY(launch_bw_wgrad(b.dg, nullptr, 1, x_rows, row_map, s.K, off, E, d_wg, I, H, st));
+    MOE_TRY(launch_bw_wgrad(b.du, nullptr, 1, x_rows, row_map, s.K, off, E, d_wu, I, H, st));
+#undef MOE_TRY
+    return hipSuccess;
+}
+
+}  // namespace
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+moe_status_t moe_backward_workspace_bytes(const moe_shape_t *shape, size_t *out_bytes) {
+    moe_status_t st = check_bw_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!out_bytes) return MOE_ERR_NULL;
+    *out_bytes = carve_bw(*shape, nullptr).total;
+    return MOE_OK;
+}
+
+moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x_perm, const int32_t *expert_offsets,
+                                         const void *w_gate, const void *w_up, const void *w_down, const void *dy_perm,
+                                         void *d_x_perm, float *d_w_gate, float *d_w_up, float *d_w_down,
+                                         void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_bw_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!x_perm || !expert_offsets || !w_gate || !w_up || !w_down || !dy_perm || !d_x_perm || !d_w_gate || !d_w_up || !d_w_down)
+        return MOE_ERR_NULL;
+    if (misaligned(x_perm) || misaligned(expert_offsets) || misaligned(w_gate) || misaligned(w_up) || misaligned(w_down) ||
+        misaligned(dy_perm) || misaligned(d_x_perm) || misaligned(d_w_gate) || misaligned(d_w_up) || misaligned(d_w_down))
+        return MOE_ERR_ALIGN;
+    if (!ws) return MOE_ERR_WORKSPACE;
+    if (misaligned(ws)) return MOE_ERR_ALIGN;
+    if (ws_bytes < carve_bw(*shape, nullptr).total) return MOE_ERR_WORKSPACE;
+    hipStream_t hs = (hipStream_t)stream;
+    const moe_shape_t &s = *shape;
+    BwWorkspace b = carve_bw(s, ws);
+    if (s.T == 0) {      // no rows: the weight gradients are zero
+        const size_t cnt = (size_t)s.E * s.I * s.H;
+        if (zero_floats(d_w_gate, cnt, hs) != hipSuccess || zero_floats(d_w_up, cnt, hs) != hipSuccess ||
+            zero_floats(d_w_down, cnt, hs) != hipSuccess)
+            return MOE_ERR_HIP;
+        return MOE_OK;
+    }
+    return expert_backward(s, (const bf16_t *)x_perm, (const bf16_t *)dy_perm, nullptr, nullptr, expert_offsets,
+                           (const bf16_t *)w_gate, (const bf16_t *)w_up, (const bf16_t *)w_down, b, (bf16_t *)d_x_perm,
+                           d_w_gate, d_w_up, d_w_down, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                          const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                          void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                          float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_bw_shape(shape);
+    if (st != MOE_OK) return st;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !d_out || !d_x || !d_w_router || !d_w_gate || !d_w_up || !d_w_down)
+        return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
+        misaligned(w_down) || misaligned(d_out) || misaligned(d_x) || misaligned(d_w_router) || misaligned(d_router_bias) ||
+        misaligned(d_w_gate) || misaligned(d_w_up) || misaligned(d_w_down))
+        return MOE_ERR_ALIGN;
+    if (!ws) return MOE_ERR_WORKSPACE;
+    if (misaligned(ws)) return MOE_ERR_ALIGN;
+    if (ws_bytes < carve_bw(*shape, nullptr).total) return MOE_ERR_WORKSPACE;
+    hipStream_t hs = (hipStream_t)stream;
+    const moe_shape_t &s = *shape;
+    BwWorkspace b = carve_bw(s, ws);
+    Workspace &w = b.fwd;
+    if (s.T == 0) {
+        const size_t cnt = (size_t)s.E * s.I * s.H;
+        if (zero_floats(d_w_gate, cnt, hs) != hipSuccess || zero_floats(d_w_up, cnt, hs) != hipSuccess ||
+            zero_floats(d_w_down, cnt, hs) != hipSuccess || zero_floats(d_w_router, (size_t)s.E * s.H, hs) != hipSuccess ||
+            zero_floats(d_router_bias, (size_t)s.E, hs) != hipSuccess)
+            return MOE_ERR_HIP;
+        return MOE_OK;
+    }
+    const bf16_t *xb = (const bf16_t *)x;
+    bf16_t *dxp = (bf16_t *)w.y_perm;
+    if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (expert_backward(s, xb, (const bf16_t *)d_out, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
+                        (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, w.topk_idx, (const bf16_t *)w_router,
+                       (bf16_t *)d_x, s.H, s.K);
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(64), 0, hs, xb, b.dl, w.row_to_assign,
+                       w.expert_offsets, d_w_router, d_router_bias, s.H, s.K);
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+}  // extern "C"

@@ -34,6 +34,11 @@ __global__ __launch_bounds__(1024) void build_tile_map_kernel(const int32_t *__r
     }
 }
 
+hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st) {
+    hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, st, off, E, tile_rows, max_tiles, tile_map);
+    return hipGetLastError();
+}
+
 // ---- global -> register staging of 8 consecutive elements as packed bf16 -------------------
 __device__ __forceinline__ u32x4 load8_bf16(const bf16_t *p, bool ok) {
     u32x4 v = {0u, 0u, 0u, 0u};

@@ -7,7 +7,7 @@ import re
 import pytest
 
 from paper_2511_11373_amd import build as hip_build
-from paper_2511_11373_amd import grpo, moe
+from paper_2511_11373_amd import grpo, moe, moe_backward
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -23,6 +23,10 @@ def test_every_declared_symbol_is_exported(lib):
     hdr = open(os.path.join(ROOT, "include", "moe_ffn.h")).read()
     declared = set(re.findall(r"\b(moe_[a-z_]+)\s*\(", hdr))
     assert declared == set(moe.EXPORTS)
+    hdr_b = open(os.path.join(ROOT, "include", "moe_ffn_backward.h")).read()
+    declared_b = set(re.findall(r"\b(moe_[a-z_]+)\s*\(", hdr_b))
+    assert declared_b == set(moe_backward.EXPORTS)
+    declared |= declared_b
     for name in declared:
         assert getattr(lib, name) is not None
     assert lib.moe_status_string(0) == b"ok" and lib.moe_status_string(2) == b"unsupported shape"
@@ -126,3 +130,32 @@ def test_grpo_symbols_and_validation(lib):
     assert lib.grpo_token_logprob(ctypes.byref(empty), a[0], a[1], a[2], None) == 0
     assert lib.grpo_logprob_objective(ctypes.byref(empty), *a[:11], None) == 0
     assert lib.grpo_token_logprob(None, a[0], a[1], a[2], None) == 1
+
+
+def test_backward_validation_on_the_host(lib):
+    vp = ctypes.c_void_p
+    moe_backward._lib()
+    a = [vp(0x1000 * (i + 1)) for i in range(14)]
+    good = moe.make_shape(4, 64, 8, 2, 32, moe.MOE_BF16)
+    need = ctypes.c_size_t(0)
+    assert lib.moe_backward_workspace_bytes(ctypes.byref(good), ctypes.byref(need)) == 0
+    assert need.value % 256 == 0 and need.value > moe.workspace_bytes(good)
+    for shape, code in ((moe.make_shape(4, 64, 8, 2, 32, moe.MOE_F32), 3), (moe.make_shape(4, 64, 8, 2, 32, moe.MOE_BF16, False), 2),
+                        (moe.make_shape(4, 60, 8, 2, 32, moe.MOE_BF16), 2), (moe.make_shape(4, 64, 8, 9, 32, moe.MOE_BF16), 2)):
+        assert lib.moe_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)) == code
+        assert lib.moe_backward(ctypes.byref(shape), *a, 1 << 40, None) == code
+        assert lib.moe_grouped_swiglu_backward(ctypes.byref(shape), *a[:11], 1 << 40, None) == code
+    # required pointers, alignment, workspace
+    for i in (0, 1, 3, 4, 5, 6, 7, 8, 10, 11, 12):
+        b = list(a)
+        b[i] = None
+        assert lib.moe_backward(ctypes.byref(good), *b, 1 << 40, None) == 1, i
+    b = list(a)
+    b[2] = None       # the bias and its gradient are optional
+    b[9] = None
+    b[13] = None      # ... the workspace is not
+    assert lib.moe_backward(ctypes.byref(good), *b, 1 << 40, None) == 4
+    b = list(a)
+    b[6] = vp(0x7004)
+    assert lib.moe_backward(ctypes.byref(good), *b, 1 << 40, None) == 5
+    assert lib.moe_backward(ctypes.byref(good), *a, need.value - 1 if need.value else 0, None) in (4,)

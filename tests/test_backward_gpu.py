@@ -1,0 +1,98 @@
+"""GPU parity of the backward pass against the float64 oracle, through the C ABI.
+
+Tolerances: the library rounds g, u, d_out*Wd, dg, du and w*a to bf16 (relative 2^-9 each) and sums in float, so
+every gradient carries a few independent roundings per term: relative L2 error of a few 1e-3 expected, bound 1e-2;
+largest single deviation bounded by 2e-2 of the largest magnitude of the tensor.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_backward_oracle as bwd
+from paper_2511_11373_amd import moe, moe_backward as mb
+from paper_2511_11373_amd import workloads as wl
+from gpu_util import check_close, host, shape_of, to_dev, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_normal(rng, shape, scale=1.0):
+    bits = wl.f32_to_bf16_bits_numpy((rng.standard_normal(shape) * scale).astype(np.float32))
+    return bits, wl.bf16_bits_to_f32(bits)
+
+
+def _cmp(got, ref, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = max(np.abs(ref).max(), 1e-30)
+    return check_close(host(got), ref, what, max_abs=2e-2 * scale, rel_l2=1e-2)
+
+
+def test_grouped_swiglu_backward_uneven_segments(oracle_lib):
+    counts = [0, 70, 0, 33, 256, 1, 300, 0]
+    n, H, I, E = sum(counts), 136, 72, len(counts)
+    cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=41, sigma_w=0.1)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    rng = np.random.default_rng(41)
+    dy_bits, dy = _bf16_normal(rng, (n, H))
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    shp = shape_of(cfg)
+    ws = mb.alloc_workspace(shp)
+    out = mb.moe_grouped_swiglu_backward(shp, g["x"], torch.from_numpy(off).cuda(), g["w_gate"], g["w_up"], g["w_down"],
+                                         to_dev(dy_bits, wl.BF16), ws)
+    ref = bwd.grouped_swiglu_backward(d["x_f32"], off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], dy)
+    for name in ("d_x_perm", "d_w_gate", "d_w_up", "d_w_down"):
+        _cmp(out[name], ref[name], name)
+    # experts without rows get exact zeros
+    for e in (0, 2, 7):
+        assert torch.count_nonzero(out["d_w_gate"][e]).item() == 0 and torch.count_nonzero(out["d_w_down"][e]).item() == 0
+
+
+CASES = [
+    wl.small_config(37, 72, 5, 3, 40, dtype=wl.BF16, seed=42, sigma_w=0.1),          # nothing divides a tile
+    wl.small_config(300, 256, 16, 4, 128, dtype=wl.BF16, seed=43, sigma_w=0.05),
+    wl.small_config(64, 128, 40, 8, 64, dtype=wl.BF16, seed=44, sigma_w=0.1),         # most experts get one or two rows
+    wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=45, sigma_w=0.05),      # large-batch router, several row tiles
+]
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
+def test_backward_against_oracle(oracle_lib, cfg):
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    rng = np.random.default_rng(cfg.seed)
+    bias = (rng.standard_normal(cfg.E) * 0.1).astype(np.float32) if cfg.seed % 2 else None
+    do_bits, do = _bf16_normal(rng, (cfg.T, cfg.H))
+    shp = shape_of(cfg)
+    ws = mb.alloc_workspace(shp)
+    bias_dev = None if bias is None else torch.from_numpy(bias).cuda()
+    out = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    o_idx, _ = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K, bias)
+    ref = bwd.backward(d["x_f32"], d["w_router_f32"], bias, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx, do, True)
+    for name in ("d_x", "d_w_router", "d_router_bias", "d_w_gate", "d_w_up", "d_w_down"):
+        _cmp(out[name], ref[name], name)
+    # a second call gives the same bits
+    out2 = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    for name in out:
+        assert torch.equal(out[name], out2[name]), name
+
+
+def test_backward_restrictions_and_empty_batch():
+    shp = moe.make_shape(8, 64, 4, 2, 32, moe.MOE_F32)
+    with pytest.raises(moe.MoeError) as e:
+        mb.workspace_bytes(shp)
+    assert e.value.code == 3
+    shp = moe.make_shape(8, 64, 4, 2, 32, moe.MOE_BF16, renormalize=False)
+    with pytest.raises(moe.MoeError) as e:
+        mb.workspace_bytes(shp)
+    assert e.value.code == 2
+    shp = moe.make_shape(0, 64, 4, 2, 32, moe.MOE_BF16)
+    ws = mb.alloc_workspace(shp)
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    out = {k: torch.ones(v, dtype=torch.float32, device="cuda") for k, v in
+           (("d_w_router", (4, 64)), ("d_router_bias", (4,)), ("d_w_gate", (4, 32, 64)), ("d_w_up", (4, 32, 64)), ("d_w_down", (4, 64, 32)))}
+    out["d_x"] = z(1, 64)      # never written: there is no token (a zero-size tensor would have a NULL pointer)
+    mb.moe_backward(shp, z(1, 64), z(4, 64), None, z(4, 32, 64), z(4, 32, 64), z(4, 64, 32), z(1, 64), ws, out=out)
+    torch.cuda.synchronize()
+    for name in ("d_w_router", "d_router_bias", "d_w_gate", "d_w_up", "d_w_down"):
+        assert torch.count_nonzero(out[name]).item() == 0, name
