@@ -17,13 +17,11 @@
 
 namespace moe {
 
-hipError_t launch_bw_rows_kfast(const bf16_t *rows, const int32_t *row_map, int row_div, const bf16_t *w, const int32_t *off,
+hipError_t launch_bw_rows_kfast(const bf16_t *rows, const bf16_t *w, const int32_t *off, const int32_t *tile_map, int max_tiles,
+                                bf16_t *out, int KD, int N, hipStream_t st);
+hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1, const int32_t *off,
                                 const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st);
-hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const int32_t *row_map, int row_div, const bf16_t *w0,
-                                const bf16_t *w1, const int32_t *off, const int32_t *tile_map, int max_tiles, bf16_t *out,
-                                int KD, int N, hipStream_t st);
-hipError_t launch_bw_wgrad(const bf16_t *P, const int32_t *p_map, int p_div, const bf16_t *Q, const int32_t *q_map, int q_div,
-                           const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
+hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
 hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
 
 namespace {
@@ -165,6 +163,7 @@ hipError_t zero_floats(float *p, size_t count, hipStream_t st) {
 struct BwWorkspace {
     Workspace fwd;          // routing, permutation, tile list; fwd.act holds g, fwd.y_perm holds the row gradients dxp
     bf16_t *u, *dq, *dg, *du, *aw;      // [n][I] each
+    bf16_t *x_perm, *up_perm;           // [n][H] each: x and d_out copied into expert-sorted row order
     float *dw_row, *dl;                 // [n] each
     size_t total;
 };
@@ -183,6 +182,8 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.dg, n * s.I * 2);
     take(b.du, n * s.I * 2);
     take(b.aw, n * s.I * 2);
+    take(b.x_perm, n * s.H * 2);
+    take(b.up_perm, n * s.H * 2);
     take(b.dw_row, n * 4);
     take(b.dl, n * 4);
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
@@ -201,8 +202,9 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
     return MOE_OK;
 }
 
-// The expert part: rows are x (gathered through row_map / K) or x_perm; up = d_out (gathered) or dy_perm.
-hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_map,
+// The expert part over expert-sorted rows: x_rows [n][H], up_rows [n][H] = the upstream gradient of each row's y
+// (without the routing weight when topk_w is given: the weight of row r is then topk_w[row_to_assign[r]]).
+hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_to_assign,
                            const float *topk_w, const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
                            BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu, float *d_wd, hipStream_t st) {
     const int n = s.T * s.K, H = s.H, I = s.I, E = s.E;
@@ -212,16 +214,16 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     hipError_t err;
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
-    MOE_TRY(launch_bw_rows_kfast(x_rows, row_map, s.K, wg, off, tiles, max_tiles, g, H, I, st));
-    MOE_TRY(launch_bw_rows_kfast(x_rows, row_map, s.K, wu, off, tiles, max_tiles, b.u, H, I, st));
-    MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, row_map, s.K, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
-    hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_map, b.dg, b.du, b.aw,
+    MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
+    MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
+    MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
+    hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
-    MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, nullptr, 1, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
-    MOE_TRY(launch_bw_wgrad(up_rows, row_map, s.K, b.aw, nullptr, 1, off, E, d_wd, H, I, st));
-    MOE_TRY(launch_bw_wgrad(b.dg, nullptr, 1, x_rows, row_map, s.K, off, E, d_wg, I, H, st));
-    MOE_TRY(launch_bw_wgrad(b.du, nullptr, 1, x_rows, row_map, s.K, off, E, d_wu, I, H, st));
+    MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
+    MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
+    MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
+    MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
 #undef MOE_TRY
     return hipSuccess;
 }
@@ -302,7 +304,11 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
     if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
     if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
-    if (expert_backward(s, xb, (const bf16_t *)d_out, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
+    // x and d_out in expert-sorted row order, so that the GEMMs address their rows by plain arithmetic
+    if (launch_gather_rows(s, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
+        launch_gather_rows(s, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (expert_backward(s, b.x_perm, b.up_perm, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
                         (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs) != hipSuccess)
         return MOE_ERR_HIP;
     hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);

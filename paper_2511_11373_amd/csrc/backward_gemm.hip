@@ -47,31 +47,26 @@ __device__ __forceinline__ u32x4 load16(const bf16_t *p, bool ok) {
 //                  j = 0..7, indices k0 + 8q .. +7.
 //   KSLOW = true : stored [reduction][ld] with the rows contiguous; lane (i, q) loads reduction indices
 //                  k0 + 8q + jj, jj = 0..7, rows row0 + 8 i .. +7, and transposes.
-// Rows >= row_end and reduction indices >= k_end read as zero.  `map`/`div` gather the stored row (KSLOW: the
-// stored reduction row) through map[.] / div.
+// Rows >= row_end and reduction indices >= k_end read as zero.  Addresses are plain arithmetic (gathered rows are
+// copied into place beforehand), so a step's loads can be issued without waiting for anything.
 template <bool KSLOW>
 struct Operand {
     const bf16_t *base;
-    const int32_t *map;
-    int div, ld;
+    int ld;
     __device__ __forceinline__ void fetch(u32x4 (&raw)[8], int row0, int row_end, int k0, int k_end, int i, int q) const {
         if (KSLOW) {
             const int r = row0 + 8 * i;
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
                 const int k = k0 + 8 * q + jj;
-                const bool ok = k < k_end && r < row_end;       // rows come in whole groups of 8 (row counts are multiples of 8)
-                const int src = ok && map ? map[k] / div : k;
-                raw[jj] = load16(base + (size_t)src * ld + r, ok);
+                raw[jj] = load16(base + (size_t)k * ld + r, k < k_end && r < row_end);   // row counts are multiples of 8
             }
         } else {
             const int k = k0 + 8 * q;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int r = row0 + 8 * i + j;
-                const bool ok = r < row_end && k < k_end;       // the reduction length is a multiple of 8
-                const int src = ok && map ? map[r] / div : r;
-                raw[j] = load16(base + (size_t)src * ld + k, ok);
+                raw[j] = load16(base + (size_t)r * ld + k, r < row_end && k < k_end);    // the reduction length is a multiple of 8
             }
         }
     }
@@ -105,10 +100,9 @@ __device__ __forceinline__ void reduce_range(f32x4 (&acc)[8][8], const Operand<A
     for (int k0 = k_begin; k0 < k_end; k0 += 32) {
         A.finish(ra, oa);
         B.finish(rb, ob);
-        if (k0 + 32 < k_end) {          // the raw registers are free again: the next step's loads fly during the MFMAs
-            A.fetch(ra, row0a, enda, k0 + 32, k_end, i, q);
-            B.fetch(rb, row0b, endb, k0 + 32, k_end, i, q);
-        }
+        // the raw registers are free again: the next step's loads fly during the MFMAs (past k_end they are masked off)
+        A.fetch(ra, row0a, enda, k0 + 32, k_end, i, q);
+        B.fetch(rb, row0b, endb, k0 + 32, k_end, i, q);
         mfma_8x8(acc, oa, ob);
     }
 }
@@ -146,7 +140,6 @@ __device__ __forceinline__ void store_tile(const f32x4 (&acc)[8][8], OutT *out, 
 // Row tiles of BT rows come from the (expert, first row) list the tiled forward kernels use.
 template <bool W_KSLOW, typename OutT>
 __global__ __launch_bounds__(256, 1) void bw_rows_kernel(const bf16_t *__restrict__ a0, const bf16_t *__restrict__ a1,
-                                                         const int32_t *__restrict__ row_map, int row_div,
                                                          const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1,
                                                          const int32_t *__restrict__ off, const int32_t *__restrict__ tile_map,
                                                          int max_tiles, OutT *__restrict__ out, int KD, int N) {
@@ -163,21 +156,24 @@ __global__ __launch_bounds__(256, 1) void bw_rows_kernel(const bf16_t *__restric
         for (int jb = 0; jb < 8; ++jb) acc[ja][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const size_t wsz = (size_t)KD * N;
     for (int p = 0; p < (a1 ? 2 : 1); ++p) {
-        const Operand<false> A{p ? a1 : a0, row_map, row_div, KD};
-        const Operand<W_KSLOW> B{(p ? w1 : w0) + (size_t)e * wsz, nullptr, 1, W_KSLOW ? N : KD};
+        const Operand<false> A{p ? a1 : a0, KD};
+        const Operand<W_KSLOW> B{(p ? w1 : w0) + (size_t)e * wsz, W_KSLOW ? N : KD};
         reduce_range<false, W_KSLOW>(acc, A, r0, row_end, B, n0, N, 0, KD, i, q);
     }
     store_tile<OutT>(acc, out, (size_t)N, r0, row_end, n0, N, i, q);
 }
 
 // ---- weight gradients: out[e][m][n] = sum over the rows r of expert e of P[r][m] * Q[r][n] ---------------------------
-// Both operands are stored by row r; either may be gathered (stored row = map[r] / div).  Experts without rows get zeros.
-__global__ __launch_bounds__(256, 1) void bw_wgrad_kernel(const bf16_t *__restrict__ P, const int32_t *__restrict__ p_map, int p_div,
-                                                          const bf16_t *__restrict__ Q, const int32_t *__restrict__ q_map, int q_div,
+// Both operands are stored by row r.  Experts without rows get zeros.
+__global__ __launch_bounds__(256, 1) void bw_wgrad_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Q,
                                                           const int32_t *__restrict__ off, float *__restrict__ out, int M, int N,
-                                                          int n_tiles_n) {
-    const int e = blockIdx.y;
-    const int mt = blockIdx.x / n_tiles_n, nt = blockIdx.x - mt * n_tiles_n;
+                                                          int n_tiles_n, int tiles_per_expert, int E) {
+    // blocks go round-robin to the 8 XCDs: all tiles of an expert are dealt to one XCD, whose L2 then serves the
+    // re-reads of the expert's rows by its other tiles
+    const int slot = blockIdx.x >> 3;
+    const int e = (slot / tiles_per_expert) * 8 + (blockIdx.x & 7), tile = slot % tiles_per_expert;
+    if (e >= E) return;
+    const int mt = tile / n_tiles_n, nt = tile - mt * n_tiles_n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = lane & 15, q = lane >> 4;
     const int m0 = mt * BT + (wave & 1) * 128, n0 = nt * BT + (wave >> 1) * 128;
     if (m0 >= M || n0 >= N) return;
@@ -186,8 +182,8 @@ __global__ __launch_bounds__(256, 1) void bw_wgrad_kernel(const bf16_t *__restri
     for (int ja = 0; ja < 8; ++ja)
 #pragma unroll
         for (int jb = 0; jb < 8; ++jb) acc[ja][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const Operand<true> A{P, p_map, p_div, M};
-    const Operand<true> B{Q, q_map, q_div, N};
+    const Operand<true> A{P, M};
+    const Operand<true> B{Q, N};
     reduce_range<true, true>(acc, A, m0, M, B, n0, N, off[e], off[e + 1], i, q);
     store_tile<float>(acc, out + (size_t)e * M * N, (size_t)N, m0, M, n0, N, i, q);
 }
@@ -195,30 +191,26 @@ __global__ __launch_bounds__(256, 1) void bw_wgrad_kernel(const bf16_t *__restri
 }  // namespace bw
 
 // out[r][n] = sum_k rows[r][k] * W[e][n][k]  (W_KSLOW = false)  or  sum_k rows[r][k] * W[e][k][n]  (true), optionally the
-// sum of two such products.  rows are expert-sorted (off), optionally gathered through row_map / row_div.
+// sum of two such products.  rows are expert-sorted (off).
 template <bool W_KSLOW, typename OutT>
-static hipError_t launch_rows(const bf16_t *a0, const bf16_t *a1, const int32_t *row_map, int row_div, const bf16_t *w0,
-                              const bf16_t *w1, const int32_t *off, const int32_t *tile_map, int max_tiles, OutT *out,
-                              int KD, int N, hipStream_t st) {
+static hipError_t launch_rows(const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1, const int32_t *off,
+                              const int32_t *tile_map, int max_tiles, OutT *out, int KD, int N, hipStream_t st) {
     dim3 grid(max_tiles, (N + bw::BT - 1) / bw::BT);
-    hipLaunchKernelGGL((bw::bw_rows_kernel<W_KSLOW, OutT>), grid, dim3(256), 0, st, a0, a1, row_map, row_div, w0, w1, off,
-                       tile_map, max_tiles, out, KD, N);
+    hipLaunchKernelGGL((bw::bw_rows_kernel<W_KSLOW, OutT>), grid, dim3(256), 0, st, a0, a1, w0, w1, off, tile_map, max_tiles, out, KD, N);
     return hipGetLastError();
 }
 
-hipError_t launch_bw_rows_kfast(const bf16_t *rows, const int32_t *row_map, int row_div, const bf16_t *w, const int32_t *off,
+hipError_t launch_bw_rows_kfast(const bf16_t *rows, const bf16_t *w, const int32_t *off, const int32_t *tile_map, int max_tiles,
+                                bf16_t *out, int KD, int N, hipStream_t st) {
+    return launch_rows<false, bf16_t>(rows, nullptr, w, nullptr, off, tile_map, max_tiles, out, KD, N, st);
+}
+hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1, const int32_t *off,
                                 const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st) {
-    return launch_rows<false, bf16_t>(rows, nullptr, row_map, row_div, w, nullptr, off, tile_map, max_tiles, out, KD, N, st);
+    return launch_rows<true, bf16_t>(a0, a1, w0, w1, off, tile_map, max_tiles, out, KD, N, st);
 }
-hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const int32_t *row_map, int row_div, const bf16_t *w0,
-                                const bf16_t *w1, const int32_t *off, const int32_t *tile_map, int max_tiles, bf16_t *out,
-                                int KD, int N, hipStream_t st) {
-    return launch_rows<true, bf16_t>(a0, a1, row_map, row_div, w0, w1, off, tile_map, max_tiles, out, KD, N, st);
-}
-hipError_t launch_bw_wgrad(const bf16_t *P, const int32_t *p_map, int p_div, const bf16_t *Q, const int32_t *q_map, int q_div,
-                           const int32_t *off, int E, float *out, int M, int N, hipStream_t st) {
+hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off, int E, float *out, int M, int N, hipStream_t st) {
     const int tm = (M + bw::BT - 1) / bw::BT, tn = (N + bw::BT - 1) / bw::BT;
-    hipLaunchKernelGGL(bw::bw_wgrad_kernel, dim3(tm * tn, E), dim3(256), 0, st, P, p_map, p_div, Q, q_map, q_div, off, out, M, N, tn);
+    hipLaunchKernelGGL(bw::bw_wgrad_kernel, dim3(8 * ((E + 7) / 8) * tm * tn), dim3(256), 0, st, P, Q, off, out, M, N, tn, tm * tn, E);
     return hipGetLastError();
 }
 
