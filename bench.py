@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="decode64",
-                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k"])
+                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -140,6 +140,81 @@ def bench_logprob(args):
     print(json.dumps(rec))
 
 
+def bench_backward(args):
+    """Another row of the path: the block's backward pass at the trainer's batch (Section 4.1: the policy is
+    optimised with AdamW, so every RL step differentiates this layer).  One step = one moe_backward call on the
+    prefill16k inputs and a random upstream gradient; bound by the bf16 matrix cores."""
+    import torch
+    from paper_2511_11373_amd import moe, moe_backward as mb
+    from paper_2511_11373_amd import workloads as wl
+    cfg = wl.CONFIGS["prefill16k"]
+    steps = args.steps if args.steps is not None else 10
+    warmup = args.warmup if args.warmup is not None else 2
+    want_cpu = not args.no_cpu_baseline
+    d = wl.make_inputs(cfg, want_f32=want_cpu)
+
+    def dev(a):
+        return torch.from_numpy(a).view(torch.bfloat16).cuda()
+    x, wr, wg, wu, wd = (dev(d[k]) for k in ("x", "w_router", "w_gate", "w_up", "w_down"))
+    rng = np.random.default_rng(cfg.seed + 1000)
+    do_f32 = rng.standard_normal((cfg.T, cfg.H), dtype=np.float32)
+    do_bits = wl.f32_to_bf16_bits(do_f32)
+    d_out = dev(do_bits)
+    shp = moe.make_shape(cfg.T, cfg.H, cfg.E, cfg.K, cfg.I, moe.MOE_BF16, True)
+    ws = mb.alloc_workspace(shp)
+    out = mb.moe_backward(shp, x, wr, None, wg, wu, wd, d_out, ws)
+    for _ in range(warmup):
+        mb.moe_backward(shp, x, wr, None, wg, wu, wd, d_out, ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        mb.moe_backward(shp, x, wr, None, wg, wu, wd, d_out, ws, out=out)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    stage = np.zeros(mb.NUM_STAGES)
+    n_prof = max(3, min(steps, 10))
+    for _ in range(n_prof):
+        stage += np.array(mb.moe_backward_stage_times(shp, x, wr, None, wg, wu, wd, d_out, ws, out))
+    stage /= n_prof
+    stages_ms = {n: round(float(v), 5) for n, v in zip(mb.STAGE_NAMES, stage)}
+    empty = stage[mb.STAGE_NAMES.index("empty_interval")]
+    # the dominant kernel: the weight-gradient GEMM (three launches per step, each 2 * T*K * H * I flop)
+    wg_ms = float(np.mean([stage[mb.STAGE_NAMES.index(k)] for k in ("d_w_down", "d_w_gate", "d_w_up")]) - empty)
+    wg_flops = 2.0 * cfg.T * cfg.K * cfg.H * cfg.I
+    ach = wg_flops / (wg_ms * 1e-3) / 1e12
+    step_flops = 8 * wg_flops          # g, u, d_out Wd, two products for the row gradients, three weight gradients
+    cpu = None
+    if want_cpu:
+        import oracle
+        from oracle import moe_backward_oracle as bwd
+        n = 2048
+        c0 = time.perf_counter()
+        o_idx, _ = oracle.route_topk(d["x_f32"][:n], d["w_router_f32"], cfg.K)
+        ref = bwd.backward(d["x_f32"][:n], d["w_router_f32"], None, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx,
+                           wl.bf16_bits_to_f32(do_bits[:n]), True)
+        dt = time.perf_counter() - c0
+        cpu = {"value": round(n / dt, 2), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"backward of the first {n} of {cfg.T} tokens as a batch of their own, 1 pass, {dt:.1f} s (numpy, float64)"}
+        # sanity of the timed path on the same sample: d_x of a token does not depend on the other tokens of the batch
+        got = out["d_x"][:n].float().cpu().numpy().astype(np.float64)
+        cpu["rel_l2_dx_gpu_vs_oracle"] = round(float(np.linalg.norm(got - ref["d_x"]) / max(np.linalg.norm(ref["d_x"]), 1e-30)), 6)
+    rec = {
+        "metric": "MoE-layer backward tokens/s + % bf16 MFMA peak", "value": round(cfg.T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "backward16k", "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.E, "top_k": cfg.K,
+                   "intermediate": cfg.I},
+        "roofline": {"bound": "mfma", "kernel": "bw_wgrad_kernel", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": wg_flops, "avg_launch_ms": round(wg_ms, 5)},
+        "cpu_baseline": cpu,
+        "layer": {"algorithmic_GFLOP": round(step_flops / 1e9, 2),
+                  "mfma_frac_whole_step": round(step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                  "stages_ms": stages_ms},
+    }
+    print(json.dumps(rec))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -156,6 +231,8 @@ def main():
     moe.load_library()          # raises if the HIP library is not built: there is no fallback
     if args.workload == "logprob16k":
         return bench_logprob(args)
+    if args.workload == "backward16k":
+        return bench_backward(args)
     cfg = wl.CONFIGS[args.workload]
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[cfg.name]
     warmup = args.warmup if args.warmup is not None else max(5, steps // 10)

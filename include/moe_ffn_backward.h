@@ -60,6 +60,22 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
                           void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
                           float *d_w_down, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * moe_backward with a HIP event recorded on `stream` at every stage boundary, for attributing the time of one
+ * call to its kernels.  Unlike the other entry points this one blocks until the call has finished on the device.
+ *   stage_ms  host float[MOE_BW_NUM_STAGES] out: elapsed milliseconds of
+ *             [0] routing (recomputed)   [1] permutation + copies of x and d_out into expert-sorted rows
+ *             [2] row-tile list   [3] g = x Wg^T   [4] u = x Wu^T   [5] dq = d_out Wd   [6] row-wise SwiGLU backward
+ *             [7] dx rows = dg Wg + du Wu   [8] dWd   [9] dWg   [10] dWu   [11] softmax backward, dx, router gradients
+ *             [12] an empty interval (two events back to back): what the measurement itself adds to a stage
+ * Same arguments, results and errors as moe_backward otherwise.
+ */
+#define MOE_BW_NUM_STAGES 13
+moe_status_t moe_backward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                      const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                      void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                                      float *d_w_down, void *ws, size_t ws_bytes, void *stream, float *stage_ms);
+
 #ifdef __cplusplus
 }
 #endif

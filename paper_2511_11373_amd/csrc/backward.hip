@@ -160,6 +160,15 @@ hipError_t zero_floats(float *p, size_t count, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Optional stage timer of the backward call: an event at every stage boundary.
+struct BwProbe {
+    hipEvent_t ev[MOE_BW_NUM_STAGES + 1];
+    int n = 0;
+    hipStream_t st = nullptr;
+    void mark() { if (n <= MOE_BW_NUM_STAGES) (void)hipEventRecord(ev[n++], st); }
+};
+inline void bw_mark(BwProbe *p) { if (p) p->mark(); }
+
 struct BwWorkspace {
     Workspace fwd;          // routing, permutation, tile list; fwd.act holds g, fwd.y_perm holds the row gradients dxp
     bf16_t *u, *dq, *dg, *du, *aw;      // [n][I] each
@@ -206,7 +215,8 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
 // (without the routing weight when topk_w is given: the weight of row r is then topk_w[row_to_assign[r]]).
 hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_to_assign,
                            const float *topk_w, const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
-                           BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu, float *d_wd, hipStream_t st) {
+                           BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu, float *d_wd, hipStream_t st,
+                           BwProbe *probe = nullptr) {
     const int n = s.T * s.K, H = s.H, I = s.I, E = s.E;
     const int max_tiles = n / kBwTile + (E < n ? E : n);
     int32_t *tiles = b.fwd.tile_map;
@@ -214,16 +224,25 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     hipError_t err;
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
+    bw_mark(probe);
     hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
+    bw_mark(probe);
     MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
+    bw_mark(probe);
     MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
+    bw_mark(probe);
 #undef MOE_TRY
     return hipSuccess;
 }
@@ -272,10 +291,10 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
                            d_w_gate, d_w_up, d_w_down, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
-                          const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
-                          void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
-                          float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
+static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                  const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                  void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                                  float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe) {
     moe_status_t st = check_bw_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !d_out || !d_x || !d_w_router || !d_w_gate || !d_w_up || !d_w_down)
@@ -301,15 +320,18 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
     }
     const bf16_t *xb = (const bf16_t *)x;
     bf16_t *dxp = (bf16_t *)w.y_perm;
+    if (probe) { probe->st = hs; probe->mark(); }
     if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
+    bw_mark(probe);
     if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
     // x and d_out in expert-sorted row order, so that the GEMMs address their rows by plain arithmetic
     if (launch_gather_rows(s, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
         launch_gather_rows(s, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess)
         return MOE_ERR_HIP;
+    bw_mark(probe);
     if (expert_backward(s, b.x_perm, b.up_perm, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
-                        (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs) != hipSuccess)
+                        (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe) != hipSuccess)
         return MOE_ERR_HIP;
     hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
@@ -319,7 +341,38 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
     hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(64), 0, hs, xb, b.dl, w.row_to_assign,
                        w.expert_offsets, d_w_router, d_router_bias, s.H, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    bw_mark(probe);
+    bw_mark(probe);       // closes the empty calibration interval
     return MOE_OK;
+}
+
+moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                          const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                          void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                          float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
+    return backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias, d_w_gate,
+                         d_w_up, d_w_down, ws, ws_bytes, stream, nullptr);
+}
+
+moe_status_t moe_backward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                      const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                      void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                                      float *d_w_down, void *ws, size_t ws_bytes, void *stream, float *stage_ms) {
+    if (!stage_ms) return MOE_ERR_NULL;
+    for (int i = 0; i < MOE_BW_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+    BwProbe probe;
+    const bool timed = shape && shape->T > 0;
+    for (int i = 0; timed && i <= MOE_BW_NUM_STAGES; ++i)
+        if (hipEventCreate(&probe.ev[i]) != hipSuccess) return MOE_ERR_HIP;
+    moe_status_t st = backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias,
+                                    d_w_gate, d_w_up, d_w_down, ws, ws_bytes, stream, timed ? &probe : nullptr);
+    if (timed && st == MOE_OK && probe.n == MOE_BW_NUM_STAGES + 1) {
+        if (hipEventSynchronize(probe.ev[MOE_BW_NUM_STAGES]) != hipSuccess) st = MOE_ERR_HIP;
+        for (int i = 0; i < MOE_BW_NUM_STAGES && st == MOE_OK; ++i)
+            if (hipEventElapsedTime(&stage_ms[i], probe.ev[i], probe.ev[i + 1]) != hipSuccess) st = MOE_ERR_HIP;
+    }
+    for (int i = 0; timed && i <= MOE_BW_NUM_STAGES; ++i) (void)hipEventDestroy(probe.ev[i]);
+    return st;
 }
 
 }  // extern "C"

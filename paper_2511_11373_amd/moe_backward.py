@@ -13,7 +13,10 @@ import torch
 from . import moe
 from .moe import MoeShape, _check, _ptr, _stream
 
-EXPORTS = ("moe_backward_workspace_bytes", "moe_grouped_swiglu_backward", "moe_backward")
+EXPORTS = ("moe_backward_workspace_bytes", "moe_grouped_swiglu_backward", "moe_backward", "moe_backward_stage_times")
+NUM_STAGES = 13
+STAGE_NAMES = ("route", "permute_copy", "tile_list", "g_gemm", "u_gemm", "dq_gemm", "swiglu_rows", "dx_rows_gemm", "d_w_down",
+               "d_w_gate", "d_w_up", "softmax_dx_router", "empty_interval")
 
 _ready = False
 
@@ -27,6 +30,7 @@ def _lib() -> ctypes.CDLL:
         lib.moe_backward_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         lib.moe_grouped_swiglu_backward.argtypes = [sp] + [vp] * 11 + [sz, vp]
         lib.moe_backward.argtypes = [sp] + [vp] * 14 + [sz, vp]
+        lib.moe_backward_stage_times.argtypes = [sp] + [vp] * 14 + [sz, vp, ctypes.POINTER(ctypes.c_float)]
         for name in EXPORTS:
             getattr(lib, name).restype = ctypes.c_int
         _ready = True
@@ -70,3 +74,13 @@ def moe_backward(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tenso
                                _ptr(w_down), _ptr(d_out), _ptr(out["d_x"]), _ptr(out["d_w_router"]), _ptr(out["d_router_bias"]),
                                _ptr(out["d_w_gate"]), _ptr(out["d_w_up"]), _ptr(out["d_w_down"]), _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+def moe_backward_stage_times(shape: MoeShape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, ws, out):
+    """moe_backward with per-stage event timing; blocks.  Returns [ms per stage]."""
+    ms = (ctypes.c_float * NUM_STAGES)()
+    _check(_lib().moe_backward_stage_times(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
+                                           _ptr(w_down), _ptr(d_out), _ptr(out["d_x"]), _ptr(out["d_w_router"]),
+                                           _ptr(out["d_router_bias"]), _ptr(out["d_w_gate"]), _ptr(out["d_w_up"]),
+                                           _ptr(out["d_w_down"]), _ptr(ws), ws.numel(), _stream(), ms))
+    return list(ms)

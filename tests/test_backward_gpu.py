@@ -77,6 +77,36 @@ def test_backward_against_oracle(oracle_lib, cfg):
         assert torch.equal(out[name], out2[name]), name
 
 
+def test_full_size_backward_on_samples(oracle_lib):
+    """The bench workload (16384 tokens, 128 experts) in the configuration bench.py times: d_x of sampled tokens (a
+    token's d_x depends on no other token) and the weight gradients of two whole experts, each computed by the
+    oracle from its own routing of the full batch."""
+    cfg = wl.CONFIGS["prefill16k"]
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    rng = np.random.default_rng(77)
+    do_bits = wl.f32_to_bf16_bits(rng.standard_normal((cfg.T, cfg.H), dtype=np.float32))
+    do = wl.bf16_bits_to_f32(do_bits)
+    shp = shape_of(cfg)
+    ws = mb.alloc_workspace(shp)
+    out = mb.moe_backward(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    o_idx, o_w = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K)
+    # d_x of sampled tokens
+    tok = np.sort(rng.choice(cfg.T, 24, replace=False))
+    ref = bwd.backward(d["x_f32"][tok], d["w_router_f32"], None, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx[tok],
+                       do[tok], True)
+    _cmp(out["d_x"][torch.from_numpy(tok).cuda()], ref["d_x"], "d_x (sampled tokens)")
+    # all three weight gradients of two experts, from every row the oracle routes to them
+    for e in (3, 101):
+        tt, kk = np.nonzero(o_idx == e)
+        dy = o_w[tt, kk].astype(np.float64)[:, None] * do[tt]
+        _, dwg, dwu, dwd = bwd.swiglu_backward_rows(d["x_f32"][tt].astype(np.float64), d["w_gate_f32"][e].astype(np.float64),
+                                                    d["w_up_f32"][e].astype(np.float64), d["w_down_f32"][e].astype(np.float64), dy)
+        _cmp(out["d_w_gate"][e], dwg, f"d_w_gate[{e}]")
+        _cmp(out["d_w_up"][e], dwu, f"d_w_up[{e}]")
+        _cmp(out["d_w_down"][e], dwd, f"d_w_down[{e}]")
+
+
 def test_backward_restrictions_and_empty_batch():
     shp = moe.make_shape(8, 64, 4, 2, 32, moe.MOE_F32)
     with pytest.raises(moe.MoeError) as e:
