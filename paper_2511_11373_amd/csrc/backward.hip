@@ -22,6 +22,11 @@ hipError_t launch_bw_rows_kfast(const bf16_t *rows, const bf16_t *w, const int32
 hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1, const int32_t *off,
                                 const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st);
 hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
+bool big_plain_applicable(int KD, int NW);
+size_t big_tile_list_bytes(const moe_shape_t &s);
+hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
+hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void *list, const bf16_t *w, bf16_t *out, int KD,
+                            int NW, hipStream_t st);
 hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
 
 namespace {
@@ -174,6 +179,7 @@ struct BwWorkspace {
     bf16_t *u, *dq, *dg, *du, *aw;      // [n][I] each
     bf16_t *x_perm, *up_perm;           // [n][H] each: x and d_out copied into expert-sorted row order
     float *dw_row, *dl;                 // [n] each
+    void *big_list;                     // per-XCD row-tile list of the forward pass's large-batch GEMM
     size_t total;
 };
 
@@ -195,6 +201,7 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.up_perm, n * s.H * 2);
     take(b.dw_row, n * 4);
     take(b.dl, n * 4);
+    take(b.big_list, big_tile_list_bytes(s));
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
     return b;
 }
@@ -224,10 +231,15 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     hipError_t err;
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
+    // the pre-activations are forward-form products: the forward pass's large-batch kernel takes them when the shape allows
+    const bool fwd_kernel = big_plain_applicable(H, I) && (long)n >= 128L * E;
+    if (fwd_kernel) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
+    if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wg, g, H, I, st));
+    else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
+    if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wu, b.u, H, I, st));
+    else MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
     bw_mark(probe);
     MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
     bw_mark(probe);

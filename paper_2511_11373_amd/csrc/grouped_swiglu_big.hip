@@ -393,4 +393,23 @@ hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows,
     return hipGetLastError();
 }
 
+// ---- the second pass's kernel as a plain grouped GEMM: out[r][f] = sum_k rows[r][k] * W[e][f][k] -------------------
+// (used by the backward pass to recompute the expert pre-activations).  Needs whole k tiles and whole weight tiles.
+bool big_plain_applicable(int KD, int NW) { return KD % big::BK == 0 && NW % big::BW == 0; }
+
+hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st) {
+    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    hipLaunchKernelGGL(build_xcd_tile_list_kernel, dim3(1), dim3(1024), 0, st, off, s.E, tiles_per_xcd, reinterpret_cast<i32x4 *>(list));
+    return hipGetLastError();
+}
+
+hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void *list, const bf16_t *w, bf16_t *out, int KD,
+                            int NW, hipStream_t st) {
+    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int nw = NW / big::BW;
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, (const int32_t *)nullptr, 1,
+                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, w, w, out, KD, NW, nw, s.T * s.K);
+    return hipGetLastError();
+}
+
 }  // namespace moe

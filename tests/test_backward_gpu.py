@@ -53,6 +53,7 @@ CASES = [
     wl.small_config(300, 256, 16, 4, 128, dtype=wl.BF16, seed=43, sigma_w=0.05),
     wl.small_config(64, 128, 40, 8, 64, dtype=wl.BF16, seed=44, sigma_w=0.1),         # most experts get one or two rows
     wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=45, sigma_w=0.05),      # large-batch router, several row tiles
+    wl.small_config(600, 256, 4, 2, 256, dtype=wl.BF16, seed=46, sigma_w=0.05),       # pre-activations by the forward pass's large-batch kernel
 ]
 
 
