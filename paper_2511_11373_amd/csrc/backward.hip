@@ -27,6 +27,11 @@ size_t big_tile_list_bytes(const moe_shape_t &s);
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
 hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void *list, const bf16_t *w, bf16_t *out, int KD,
                             int NW, hipStream_t st);
+bool bw_lds_applicable(const moe_shape_t &s);
+hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
+                              const void *list, bf16_t *out, int KD, int N, hipStream_t st);
+hipError_t launch_bw_lds_wgrad(const moe_shape_t &s, const bf16_t *P, const bf16_t *Q, const int32_t *off, float *out, int M, int N,
+                               hipStream_t st);
 hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
 
 namespace {
@@ -233,7 +238,8 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
     // the pre-activations are forward-form products: the forward pass's large-batch kernel takes them when the shape allows
     const bool fwd_kernel = big_plain_applicable(H, I) && (long)n >= 128L * E;
-    if (fwd_kernel) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
+    const bool lds_kernels = bw_lds_applicable(s);      // large batches: the LDS-pipelined GEMMs
+    if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     bw_mark(probe);
     if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wg, g, H, I, st));
     else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
@@ -241,19 +247,24 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wu, b.u, H, I, st));
     else MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.dq, H, I, st));
+    else MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
     bw_mark(probe);
     hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
     bw_mark(probe);
-    MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, b.dg, b.du, wg, wu, b.big_list, dxp, I, H, st));
+    else MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, up_rows, b.aw, off, d_wd, H, I, st));
+    else MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.dg, x_rows, off, d_wg, I, H, st));
+    else MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
     bw_mark(probe);
-    MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.du, x_rows, off, d_wu, I, H, st));
+    else MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
     bw_mark(probe);
 #undef MOE_TRY
     return hipSuccess;

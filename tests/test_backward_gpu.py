@@ -27,9 +27,11 @@ def _cmp(got, ref, what):
     return check_close(host(got), ref, what, max_abs=2e-2 * scale, rel_l2=1e-2)
 
 
-def test_grouped_swiglu_backward_uneven_segments(oracle_lib):
-    counts = [0, 70, 0, 33, 256, 1, 300, 0]
-    n, H, I, E = sum(counts), 136, 72, len(counts)
+@pytest.mark.parametrize("counts,H,I", [([0, 70, 0, 33, 256, 1, 300, 0], 136, 72),
+                                        ([0, 700, 0, 257, 256, 1, 0, 900, 3, 0], 128, 64)],     # the second takes the LDS-pipelined kernels
+                         ids=["small", "large"])
+def test_grouped_swiglu_backward_uneven_segments(oracle_lib, counts, H, I):
+    n, E = sum(counts), len(counts)
     cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=41, sigma_w=0.1)
     d = wl.make_inputs(cfg)
     g = upload(cfg, d)
@@ -44,7 +46,7 @@ def test_grouped_swiglu_backward_uneven_segments(oracle_lib):
     for name in ("d_x_perm", "d_w_gate", "d_w_up", "d_w_down"):
         _cmp(out[name], ref[name], name)
     # experts without rows get exact zeros
-    for e in (0, 2, 7):
+    for e in [i for i, c in enumerate(counts) if c == 0]:
         assert torch.count_nonzero(out["d_w_gate"][e]).item() == 0 and torch.count_nonzero(out["d_w_down"][e]).item() == 0
 
 
@@ -54,6 +56,7 @@ CASES = [
     wl.small_config(64, 128, 40, 8, 64, dtype=wl.BF16, seed=44, sigma_w=0.1),         # most experts get one or two rows
     wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=45, sigma_w=0.05),      # large-batch router, several row tiles
     wl.small_config(600, 256, 4, 2, 256, dtype=wl.BF16, seed=46, sigma_w=0.05),       # pre-activations by the forward pass's large-batch kernel
+    wl.small_config(900, 192, 3, 2, 320, dtype=wl.BF16, seed=47, sigma_w=0.05),       # LDS-pipelined GEMMs, no dimension a multiple of 256
 ]
 
 
