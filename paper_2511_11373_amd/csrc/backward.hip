@@ -81,8 +81,8 @@ __global__ __launch_bounds__(256) void bw_swiglu_kernel(const bf16_t *__restrict
     if (lane == 0 && dw_row) dw_row[r] = dot;
 }
 
-// One thread per token: dl_k = w_k (dw_k - sum_j w_j dw_j), written per assignment.
-__global__ __launch_bounds__(256) void bw_softmax_kernel(const float *__restrict__ topk_w, const float *__restrict__ dw_row,
+// One thread per token: dl_k = w_k (dw_k - sum_j w_j dw_j), written per assignment and, over the dw it came from, per row.
+__global__ __launch_bounds__(256) void bw_softmax_kernel(const float *__restrict__ topk_w, float *__restrict__ dw_row,
                                                          const int32_t *__restrict__ assign_to_row, float *__restrict__ dl,
                                                          int T, int K) {
     const int t = blockIdx.x * 256 + threadIdx.x;
@@ -91,7 +91,10 @@ __global__ __launch_bounds__(256) void bw_softmax_kernel(const float *__restrict
     for (int k = 0; k < K; ++k) mean = fmaf(topk_w[(size_t)t * K + k], dw_row[assign_to_row[(size_t)t * K + k]], mean);
     for (int k = 0; k < K; ++k) {
         const size_t a = (size_t)t * K + k;
-        dl[a] = topk_w[a] * (dw_row[assign_to_row[a]] - mean);
+        const int row = assign_to_row[a];
+        const float v = topk_w[a] * (dw_row[row] - mean);
+        dl[a] = v;
+        dw_row[row] = v;        // only this thread touches the rows of its token
     }
 }
 
@@ -128,35 +131,53 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
     }
 }
 
-// Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl[a(r)] x[t(r)][h], in row order (the rows of
-// an expert are in increasing assignment order, so the sum is reproducible); block (e, 512-wide slice of h), one wave.
-__global__ __launch_bounds__(64) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x, const float *__restrict__ dl,
-                                                             const int32_t *__restrict__ row_to_assign, const int32_t *__restrict__ off,
-                                                             float *__restrict__ dwr, float *__restrict__ dbias, int H, int K) {
-    const int e = blockIdx.x, h0 = blockIdx.y * 512 + threadIdx.x * 8;
+// Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl_row[r] x_perm[r][h].  Block (e, 512-wide slice
+// of h), 4 waves: wave w sums rows r0 + w, r0 + w + 4, ... in that order, two rows in flight, and the four partial sums are
+// added in wave order, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x_perm, const float *__restrict__ dl_row,
+                                                              const int32_t *__restrict__ off, float *__restrict__ dwr,
+                                                              float *__restrict__ dbias, int H) {
+    __shared__ float part[4][64][9];
+    const int e = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h0 = blockIdx.y * 512 + lane * 8;
+    const bool live = h0 < H;
     const int r0 = off[e], r1 = off[e + 1];
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     float bsum = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const int a = row_to_assign[r];
-        const float c = dl[a];
+    auto add = [&](float c, const u32x4 &v) {
         bsum += c;
-        if (h0 < H) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)(a / K) * H + h0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc[2 * j] = fmaf(c, __uint_as_float(v[j] << 16), acc[2 * j]);
-                acc[2 * j + 1] = fmaf(c, __uint_as_float(v[j] & 0xFFFF0000u), acc[2 * j + 1]);
-            }
+        for (int j = 0; j < 4; ++j) {
+            acc[2 * j] = fmaf(c, __uint_as_float(v[j] << 16), acc[2 * j]);
+            acc[2 * j + 1] = fmaf(c, __uint_as_float(v[j] & 0xFFFF0000u), acc[2 * j + 1]);
         }
+    };
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    int r = r0 + wave;
+    for (; r + 4 < r1; r += 8) {
+        const float c0 = dl_row[r], c1 = dl_row[r + 4];
+        const u32x4 v0 = live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)r * H + h0) : zero;
+        const u32x4 v1 = live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)(r + 4) * H + h0) : zero;
+        add(c0, v0);
+        add(c1, v1);
     }
-    if (h0 < H) {
-        *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0) = f32x4{acc[0], acc[1], acc[2], acc[3]};
-        *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0 + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+    if (r < r1) add(dl_row[r], live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)r * H + h0) : zero);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[wave][lane][j] = acc[j];
+    part[wave][lane][8] = bsum;
+    __syncthreads();
+    if (wave == 0) {
+        float tot[9];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) tot[j] = ((part[0][lane][j] + part[1][lane][j]) + part[2][lane][j]) + part[3][lane][j];
+        if (live) {
+            *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0) = f32x4{tot[0], tot[1], tot[2], tot[3]};
+            *reinterpret_cast<f32x4 *>(dwr + (size_t)e * H + h0 + 4) = f32x4{tot[4], tot[5], tot[6], tot[7]};
+        }
+        if (dbias && blockIdx.y == 0 && lane == 0) dbias[e] = tot[8];
     }
-    if (dbias && blockIdx.y == 0 && threadIdx.x == 0) dbias[e] = bsum;
 }
 
 __global__ __launch_bounds__(256) void bw_zero_kernel(float *__restrict__ p, size_t count) {
@@ -183,7 +204,7 @@ struct BwWorkspace {
     Workspace fwd;          // routing, permutation, tile list; fwd.act holds g, fwd.y_perm holds the row gradients dxp
     bf16_t *u, *dq, *dg, *du, *aw;      // [n][I] each
     bf16_t *x_perm, *up_perm;           // [n][H] each: x and d_out copied into expert-sorted row order
-    float *dw_row, *dl;                 // [n] each
+    float *dw_row, *dl;                 // [n] each: <dq, a> per row (later dl per row), dl per assignment
     void *big_list;                     // per-XCD row-tile list of the forward pass's large-batch GEMM
     size_t total;
 };
@@ -341,7 +362,6 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
             return MOE_ERR_HIP;
         return MOE_OK;
     }
-    const bf16_t *xb = (const bf16_t *)x;
     bf16_t *dxp = (bf16_t *)w.y_perm;
     if (probe) { probe->st = hs; probe->mark(); }
     if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
@@ -361,8 +381,8 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, w.topk_idx, (const bf16_t *)w_router,
                        (bf16_t *)d_x, s.H, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(64), 0, hs, xb, b.dl, w.row_to_assign,
-                       w.expert_offsets, d_w_router, d_router_bias, s.H, s.K);
+    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, b.x_perm, b.dw_row, w.expert_offsets,
+                       d_w_router, d_router_bias, s.H);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);
     bw_mark(probe);       // closes the empty calibration interval
