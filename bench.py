@@ -187,13 +187,18 @@ def bench_backward(args):
     if want_cpu:
         import oracle
         from oracle import moe_backward_oracle as bwd
-        n = 2048
+        n = 8192
         c0 = time.perf_counter()
         o_idx, _ = oracle.route_topk(d["x_f32"][:n], d["w_router_f32"], cfg.K)
         ref = bwd.backward(d["x_f32"][:n], d["w_router_f32"], None, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx,
                            wl.bf16_bits_to_f32(do_bits[:n]), True)
         dt = time.perf_counter() - c0
-        cpu = {"value": round(n / dt, 2), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([1] + [int(p.get("num_threads", 1)) for p in threadpool_info()])      # numpy's BLAS threads
+        except Exception:
+            cores = 1
+        cpu = {"value": round(n / dt, 2), "unit": "tokens/s", "cores": cores, "kind": "oracle",
                "sample": f"backward of the first {n} of {cfg.T} tokens as a batch of their own, 1 pass, {dt:.1f} s (numpy, float64)"}
         # sanity of the timed path on the same sample: d_x of a token does not depend on the other tokens of the batch
         got = out["d_x"][:n].float().cpu().numpy().astype(np.float64)
@@ -204,7 +209,7 @@ def bench_backward(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "backward16k", "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.E, "top_k": cfg.K,
                    "intermediate": cfg.I},
-        "roofline": {"bound": "mfma", "kernel": "bw_wgrad_kernel", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "weight-gradient GEMM (bw_lds_kernel<true>)", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                      "flops_per_launch": wg_flops, "avg_launch_ms": round(wg_ms, 5)},
         "cpu_baseline": cpu,
