@@ -187,7 +187,7 @@ def bench_backward(args):
     if want_cpu:
         import oracle
         from oracle import moe_backward_oracle as bwd
-        n = 8192
+        n = cfg.T
         c0 = time.perf_counter()
         o_idx, _ = oracle.route_topk(d["x_f32"][:n], d["w_router_f32"], cfg.K)
         ref = bwd.backward(d["x_f32"][:n], d["w_router_f32"], None, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx,
