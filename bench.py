@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="decode64",
-                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k"])
+                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k", "sched"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -220,12 +220,62 @@ def bench_backward(args):
     print(json.dumps(rec))
 
 
+def bench_sched(args):
+    """Host-only row: the agentic rollout scheduling simulator (Sections 2.3, 3.1-3.4) on a synthetic long-tailed length
+    mix with the paper's settings (groups of 8, two picks per agent, 64k-token outputs).  One step = one simulation of
+    512 problems; reported: simulated sequences per second of the native simulator, the Python oracle beside it, and
+    what the simulation says about the schedules."""
+    from paper_2511_11373_amd import sched
+    one = 1 << 24
+    cfg = dict(problems=512, group_size=8, n_select=2, segment=16384, capacity=2048, strategy=sched.ADAPTIVE, pipeline=1, seed=2511,
+               adv_eps=1e-6, short_lo=[2000, 1000, 2000, 1000, 2000], short_hi=[16000, 8000, 16000, 8000, 16000],
+               long_hi=[65536] * 5, p_long=[one // 8] * 5, p_correct=[one * 2 // 5, 0, one // 2, 0, one // 2],
+               p_keep=[0, 0, one * 9 // 10, 0, one * 9 // 10], p_flag_wrong=[0, one * 7 // 10, 0, one * 3 // 4, 0],
+               p_flag_right=[0, one // 5, 0, one // 6, 0])
+    steps = args.steps if args.steps is not None else 20
+    warmup = args.warmup if args.warmup is not None else 2
+    for _ in range(warmup):
+        r = sched.simulate(cfg, details=False)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r = sched.simulate(cfg, details=False)
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    variants = {}
+    for name, kw in (("pipeline+segments", {}), ("pipeline, whole sequences", dict(segment=1 << 20)),
+                     ("trajectory-level, segments", dict(pipeline=0)), ("trajectory-level, whole sequences", dict(pipeline=0, segment=1 << 20))):
+        v = sched.simulate(dict(cfg, **kw), details=False)
+        variants[name] = {"mean_tokens_until_trainable": round(v["sum_wait"] / v["n_groups"], 1), "makespan_tokens": v["makespan"]}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sched_oracle as so
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < args.cpu_seconds:
+            o = so.simulate(cfg)
+            reps += 1
+        dt = time.perf_counter() - c0
+        cpu = {"value": round(len(o["items"]) * reps / dt, 1), "unit": "sequences/s", "cores": 1, "kind": "oracle",
+               "sample": f"the same 512 problems, {reps} simulation(s), {dt:.1f} s (pure Python)",
+               "same_result_as_native": bool(r["makespan"] == o["makespan"] and r["sum_wait"] == o["sum_wait"] and r["n_items"] == len(o["items"]))}
+    print(json.dumps({
+        "metric": "simulated rollout sequences/s (host-only scheduling simulator)", "value": round(r["n_items"] / (ms * 1e-3), 1),
+        "unit": "sequences/s", "n_gpus": 0, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": "sched", "problems": cfg["problems"], "group_size": 8, "n_select": 2, "segment": cfg["segment"],
+                   "decode_slots": cfg["capacity"], "strategy": "adaptive"},
+        "roofline": None, "cpu_baseline": cpu,
+        "simulation": {"sequences": r["n_items"], "groups": r["n_groups"], "tokens": r["tokens"], "early_stop_by_role": r["early_stop"],
+                       "schedules": variants}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
                          "--gpus must be 1. See DESIGN.md for how the path would shard.\n")
         sys.exit(2)
+    if args.workload == "sched":
+        return bench_sched(args)
     import torch
     from paper_2511_11373_amd import moe
     from paper_2511_11373_amd import workloads as wl

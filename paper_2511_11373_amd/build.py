@@ -1,4 +1,5 @@
-"""Builds libmoe_ffn.so in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+"""Builds libmoe_ffn.so in-tree with hipcc for gfx950 (cross-compiles without a GPU) and the host-only
+scheduling simulator libmars_sched.so with g++."""
 from __future__ import annotations
 
 import glob
@@ -8,6 +9,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libmoe_ffn.so")
+SCHED_LIB = os.path.join(PKG, "libmars_sched.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -28,7 +30,19 @@ def build(verbose: bool = False) -> str:
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
+    build_host(verbose)
     return LIB
+
+
+def build_host(verbose: bool = False) -> str:
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-I", os.path.join(ROOT, "include"),
+           os.path.join(PKG, "csrc_host", "mars_sched.cpp"), "-o", SCHED_LIB]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("g++ failed:\n" + res.stdout)
+    return SCHED_LIB
 
 
 if __name__ == "__main__":
