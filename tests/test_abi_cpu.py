@@ -7,7 +7,7 @@ import re
 import pytest
 
 from paper_2511_11373_amd import build as hip_build
-from paper_2511_11373_amd import grpo, moe, moe_backward
+from paper_2511_11373_amd import attn, grpo, moe, moe_backward
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -159,3 +159,32 @@ def test_backward_validation_on_the_host(lib):
     b[6] = vp(0x7004)
     assert lib.moe_backward(ctypes.byref(good), *b, 1 << 40, None) == 5
     assert lib.moe_backward(ctypes.byref(good), *a, need.value - 1 if need.value else 0, None) in (4,)
+
+
+def test_attention_symbols_and_validation(lib):
+    hdr = open(os.path.join(ROOT, "include", "attn_decode.h")).read()
+    declared = set(re.findall(r"\b(attn_decode[a-z_]*)\s*\(", hdr))
+    assert declared == set(attn.EXPORTS)
+    attn._lib()
+    vp = ctypes.c_void_p
+    a = [vp(0x1000 * (i + 1)) for i in range(7)]
+    good = attn.make_shape(2, 32, 4, 8, 64)
+    need = ctypes.c_size_t(0)
+    assert lib.attn_decode_workspace_bytes(ctypes.byref(good), ctypes.byref(need)) == 0 and need.value % 256 == 0 and need.value > 0
+    assert lib.attn_decode_workspace_bytes(ctypes.byref(good), None) == 1 and lib.attn_decode_workspace_bytes(None, None) == 1
+    for bad in (attn.AttnShape(2, 32, 4, 64, 8, 64), attn.AttnShape(2, 32, 5, 128, 8, 64), attn.AttnShape(2, 64, 2, 128, 8, 64),
+                attn.AttnShape(-1, 32, 4, 128, 8, 64), attn.AttnShape(2, 32, 4, 128, 8, 0)):
+        assert lib.attn_decode(ctypes.byref(bad), *a, 1 << 40, None) == 2
+    for i in range(6):
+        b = list(a)
+        b[i] = None
+        assert lib.attn_decode(ctypes.byref(good), *b, 1 << 40, None) == 1
+    b = list(a)
+    b[6] = None
+    assert lib.attn_decode(ctypes.byref(good), *b, 1 << 40, None) == 4
+    assert lib.attn_decode(ctypes.byref(good), *a, need.value - 1, None) == 4
+    b = list(a)
+    b[1] = vp(0x2008)
+    assert lib.attn_decode(ctypes.byref(good), *b, 1 << 40, None) == 5
+    empty = attn.make_shape(0, 32, 4, 8, 64)
+    assert lib.attn_decode(ctypes.byref(empty), *a, 1 << 40, None) == 0
