@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="decode64",
-                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k", "sched"])
+                    choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k", "sched", "attn64"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -220,6 +220,87 @@ def bench_backward(args):
     print(json.dumps(rec))
 
 
+def bench_attn(args):
+    """Another row of the path: one decode step of attention for 64 sequences at the paper's context lengths (Section
+    4.1: 32k-token inputs, outputs of up to 64k tokens), Qwen3-30B-A3B head geometry (32 query heads, 4 key/value heads,
+    head size 128), paged bf16 cache.  One step = one attn_decode call; bound by reading the cache once from HBM."""
+    import torch
+    from paper_2511_11373_amd import attn
+    B, Hq, Hkv, D, PAGE = 64, 32, 4, 128, 256
+    steps = args.steps if args.steps is not None else 30
+    warmup = args.warmup if args.warmup is not None else 3
+    rng = np.random.default_rng(4611)
+    lens = (32768 + rng.integers(0, 65537, B)).astype(np.int32)        # a 32k prompt plus an output somewhere on its way to 64k
+    pages_of = (lens + PAGE - 1) // PAGE
+    max_pages, need = int(pages_of.max()), int(pages_of.sum())
+    n_pages = need + 16
+    ids = rng.permutation(n_pages)[:need].astype(np.int32)
+    table = np.zeros((B, max_pages), dtype=np.int32)
+    at = 0
+    for b in range(B):
+        table[b, :pages_of[b]] = ids[at:at + pages_of[b]]
+        at += pages_of[b]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4611)
+    q = torch.randn((B, Hq, D), device="cuda", generator=gen).bfloat16()
+    k_pages = torch.empty((n_pages, Hkv, PAGE, D), dtype=torch.bfloat16, device="cuda")
+    v_pages = torch.empty((n_pages, Hkv, D, PAGE), dtype=torch.bfloat16, device="cuda")
+    for p0 in range(0, n_pages, 1024):                                  # drawn on the device, 1024 pages at a time
+        p1 = min(n_pages, p0 + 1024)
+        k_pages[p0:p1] = torch.randn((p1 - p0, Hkv, PAGE, D), device="cuda", generator=gen).bfloat16()
+        v_pages[p0:p1] = torch.randn((p1 - p0, Hkv, D, PAGE), device="cuda", generator=gen).bfloat16()
+    shp = attn.make_shape(B, Hq, Hkv, max_pages, n_pages)
+    ws = attn.alloc_workspace(shp)
+    tab_d, len_d = torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda()
+    out = attn.attn_decode(shp, q, k_pages, v_pages, tab_d, len_d, ws)
+    for _ in range(warmup):
+        attn.attn_decode(shp, q, k_pages, v_pages, tab_d, len_d, ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        attn.attn_decode(shp, q, k_pages, v_pages, tab_d, len_d, ws, out=out)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        attn.attn_decode(shp, q, k_pages, v_pages, tab_d, len_d, ws, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    k_ms = e0.elapsed_time(e1) / steps          # both kernels of the call; the merge kernel is ~1 % of it
+    nbytes = int(lens.astype(np.int64).sum()) * Hkv * D * 2 * 2 + B * Hq * D * 2 * 2
+    ach = nbytes / (k_ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import attn_oracle as ao
+        from paper_2511_11373_amd import workloads as wl
+        b = int(np.argmin(lens))
+        n = int(lens[b])
+        pg = torch.from_numpy(table[b, :pages_of[b]].astype(np.int64)).cuda()
+        kb = k_pages[pg].permute(0, 2, 1, 3).reshape(-1, Hkv, D)[:n].float().cpu().numpy()          # [n, Hkv, D]
+        vb = v_pages[pg].permute(0, 3, 1, 2).reshape(-1, Hkv, D)[:n].float().cpu().numpy()
+        qb = q[b].float().cpu().numpy()
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < args.cpu_seconds:
+            ref = ao.decode_attention(qb[None], kb[None], vb[None], [n])
+            reps += 1
+        dt = time.perf_counter() - c0
+        got = out[b].float().cpu().numpy().astype(np.float64)
+        cpu = {"value": round(reps / dt, 3), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"the shortest of the 64 sequences ({n} positions), {reps} pass(es), {dt:.1f} s (numpy, float64)",
+               "rel_l2_gpu_vs_oracle": round(float(np.linalg.norm(got - ref[0]) / np.linalg.norm(ref[0])), 6)}
+    print(json.dumps({
+        "metric": "decode-attention tokens/s + % HBM BW", "value": round(B / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "attn64", "sequences": B, "query_heads": Hq, "kv_heads": Hkv, "head_size": D,
+                   "context_min": int(lens.min()), "context_mean": int(lens.mean()), "context_max": int(lens.max()), "cache_GB": round(nbytes / 1e9, 2)},
+        "roofline": {"bound": "hbm", "kernel": "attn_chunk_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": nbytes, "avg_launch_ms": round(k_ms, 5)},
+        "cpu_baseline": cpu}))
+
+
 def bench_sched(args):
     """Host-only row: the agentic rollout scheduling simulator (Sections 2.3, 3.1-3.4) on a synthetic long-tailed length
     mix with the paper's settings (groups of 8, two picks per agent, 64k-token outputs).  One step = one simulation of
@@ -288,6 +369,8 @@ def main():
         return bench_logprob(args)
     if args.workload == "backward16k":
         return bench_backward(args)
+    if args.workload == "attn64":
+        return bench_attn(args)
     cfg = wl.CONFIGS[args.workload]
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[cfg.name]
     warmup = args.warmup if args.warmup is not None else max(5, steps // 10)
