@@ -226,29 +226,14 @@ def bench_attn(args):
     head size 128), paged bf16 cache.  One step = one attn_decode call; bound by reading the cache once from HBM."""
     import torch
     from paper_2511_11373_amd import attn
-    B, Hq, Hkv, D, PAGE = 64, 32, 4, 128, 256
+    from paper_2511_11373_amd import workloads as wl
+    cfg = wl.ATTN_CONFIGS["attn64"]
+    B, Hq, Hkv, D = cfg.B, cfg.Hq, cfg.Hkv, cfg.D
     steps = args.steps if args.steps is not None else 30
     warmup = args.warmup if args.warmup is not None else 3
-    rng = np.random.default_rng(4611)
-    lens = (32768 + rng.integers(0, 65537, B)).astype(np.int32)        # a 32k prompt plus an output somewhere on its way to 64k
-    pages_of = (lens + PAGE - 1) // PAGE
-    max_pages, need = int(pages_of.max()), int(pages_of.sum())
-    n_pages = need + 16
-    ids = rng.permutation(n_pages)[:need].astype(np.int32)
-    table = np.zeros((B, max_pages), dtype=np.int32)
-    at = 0
-    for b in range(B):
-        table[b, :pages_of[b]] = ids[at:at + pages_of[b]]
-        at += pages_of[b]
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(4611)
-    q = torch.randn((B, Hq, D), device="cuda", generator=gen).bfloat16()
-    k_pages = torch.empty((n_pages, Hkv, PAGE, D), dtype=torch.bfloat16, device="cuda")
-    v_pages = torch.empty((n_pages, Hkv, D, PAGE), dtype=torch.bfloat16, device="cuda")
-    for p0 in range(0, n_pages, 1024):                                  # drawn on the device, 1024 pages at a time
-        p1 = min(n_pages, p0 + 1024)
-        k_pages[p0:p1] = torch.randn((p1 - p0, Hkv, PAGE, D), device="cuda", generator=gen).bfloat16()
-        v_pages[p0:p1] = torch.randn((p1 - p0, Hkv, D, PAGE), device="cuda", generator=gen).bfloat16()
+    lens, table, n_pages = wl.attn_lengths_and_table(cfg)          # a 32k prompt plus an output somewhere on its way to 64k
+    max_pages = table.shape[1]
+    q, k_pages, v_pages = wl.attn_device_inputs(cfg, n_pages)
     shp = attn.make_shape(B, Hq, Hkv, max_pages, n_pages)
     ws = attn.alloc_workspace(shp)
     tab_d, len_d = torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda()
@@ -273,12 +258,9 @@ def bench_attn(args):
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import attn_oracle as ao
-        from paper_2511_11373_amd import workloads as wl
         b = int(np.argmin(lens))
         n = int(lens[b])
-        pg = torch.from_numpy(table[b, :pages_of[b]].astype(np.int64)).cuda()
-        kb = k_pages[pg].permute(0, 2, 1, 3).reshape(-1, Hkv, D)[:n].float().cpu().numpy()          # [n, Hkv, D]
-        vb = v_pages[pg].permute(0, 3, 1, 2).reshape(-1, Hkv, D)[:n].float().cpu().numpy()
+        kb, vb = wl.attn_sequence_to_host(cfg, k_pages, v_pages, table, lens, b)
         qb = q[b].float().cpu().numpy()
         c0 = time.perf_counter()
         reps = 0

@@ -245,3 +245,66 @@ def make_grpo_inputs(cfg: GrpoConfig, rows: Optional[slice] = None) -> Dict[str,
         out["logits"] = logits
         out["logits_f32"] = logits
     return out
+
+
+# ---- decode attention over a long paged context ----------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class AttnConfig:
+    name: str
+    B: int                 # sequences decoding one token each
+    Hq: int
+    Hkv: int
+    prompt: int            # every context holds the prompt ...
+    max_new: int           # ... plus a uniformly drawn part of the output budget
+    seed: int = 4611
+    D: int = 128
+    page: int = 256
+
+
+ATTN_CONFIGS: Dict[str, AttnConfig] = {
+    # Section 4.1: inputs of 32k tokens, outputs of up to 64k; Qwen3-30B-A3B head geometry
+    "attn64": AttnConfig("attn64", 64, 32, 4, 32768, 65536),
+    "attn_small": AttnConfig("attn_small", 5, 32, 4, 300, 3000, seed=9),
+}
+
+
+def attn_lengths_and_table(cfg: AttnConfig):
+    """Context lengths, a random page assignment and the pool size (16 spare pages): lens [B], table [B, max_pages], n_pages."""
+    rng = np.random.default_rng(cfg.seed)
+    lens = (cfg.prompt + rng.integers(0, cfg.max_new + 1, cfg.B)).astype(np.int32)
+    pages_of = (lens + cfg.page - 1) // cfg.page
+    max_pages, need = int(pages_of.max()), int(pages_of.sum())
+    n_pages = need + 16
+    ids = rng.permutation(n_pages)[:need].astype(np.int32)
+    table = np.zeros((cfg.B, max_pages), dtype=np.int32)
+    at = 0
+    for b in range(cfg.B):
+        table[b, :pages_of[b]] = ids[at:at + pages_of[b]]
+        at += pages_of[b]
+    return lens, table, n_pages
+
+
+def attn_device_inputs(cfg: AttnConfig, n_pages: int):
+    """q [B, Hq, D], k_pages [n_pages, Hkv, page, D], v_pages [n_pages, Hkv, D, page]: standard normal bf16 drawn on the
+    device with torch's seeded generator (the full-size cache is several GB), 1024 pages at a time."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    q = torch.randn((cfg.B, cfg.Hq, cfg.D), device="cuda", generator=gen).bfloat16()
+    k_pages = torch.empty((n_pages, cfg.Hkv, cfg.page, cfg.D), dtype=torch.bfloat16, device="cuda")
+    v_pages = torch.empty((n_pages, cfg.Hkv, cfg.D, cfg.page), dtype=torch.bfloat16, device="cuda")
+    for p0 in range(0, n_pages, 1024):
+        p1 = min(n_pages, p0 + 1024)
+        k_pages[p0:p1] = torch.randn((p1 - p0, cfg.Hkv, cfg.page, cfg.D), device="cuda", generator=gen).bfloat16()
+        v_pages[p0:p1] = torch.randn((p1 - p0, cfg.Hkv, cfg.D, cfg.page), device="cuda", generator=gen).bfloat16()
+    return q, k_pages, v_pages
+
+
+def attn_sequence_to_host(cfg: AttnConfig, k_pages, v_pages, table, lens, b: int):
+    """The logical cache of sequence b as float arrays k, v [n, Hkv, D] (copied back from the device pools)."""
+    import torch
+    n = int(lens[b])
+    pg = torch.from_numpy(table[b, :(n + cfg.page - 1) // cfg.page].astype(np.int64)).to(k_pages.device)
+    k = k_pages[pg].permute(0, 2, 1, 3).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
+    v = v_pages[pg].permute(0, 3, 1, 2).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
+    return k, v

@@ -73,6 +73,23 @@ def test_decode_attention_against_oracle(lens, Hq, Hkv):
             assert np.all(got[b] == 0.0)
 
 
+@pytest.mark.parametrize("name", ["attn_small", "attn64"])
+def test_bench_workload_on_sampled_sequences(name):
+    """The bench workload in the configuration bench.py times (64 sequences of 34k-96k positions, 8 GB of cache drawn on the
+    device): the shortest, the longest and one other sequence, every head, against the oracle on the copied-back cache."""
+    cfg = wl.ATTN_CONFIGS[name]
+    lens, table, n_pages = wl.attn_lengths_and_table(cfg)
+    q, k_pages, v_pages = wl.attn_device_inputs(cfg, n_pages)
+    shp = attn.make_shape(cfg.B, cfg.Hq, cfg.Hkv, table.shape[1], n_pages)
+    ws = attn.alloc_workspace(shp)
+    out = attn.attn_decode(shp, q, k_pages, v_pages, torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda(), ws)
+    got = host(out)
+    for b in sorted({int(np.argmin(lens)), int(np.argmax(lens)), cfg.B // 2}):
+        k, v = wl.attn_sequence_to_host(cfg, k_pages, v_pages, table, lens, b)
+        ref = ao.decode_attention(q[b].float().cpu().numpy()[None], k[None], v[None], [int(lens[b])])[0]
+        check_close(got[b], ref, f"sequence {b}", max_abs=2e-2 * np.abs(ref).max(), rel_l2=1e-2)
+
+
 def test_unused_positions_and_table_entries_are_never_followed():
     # NaN in every cache position past the sequence ends and invalid page ids in the unused table entries
     got, _ = run_case(5, [1, 70, 300, 2100], 32, 4, poison=True)
