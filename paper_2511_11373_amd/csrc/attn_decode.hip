@@ -54,21 +54,27 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
     for (int c8 = 0; c8 < 8; ++c8) acc[c8] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int steps = min(CHUNK, n - tok0 + STEP - 1) / STEP;         // steps of this chunk that hold a valid position
-    for (int s = wave; s < steps; s += 4) {
-        const int t0 = tok0 + s * STEP;                                // first position of the step
-        const int page = block_table[(size_t)b * max_pages + (t0 >> 8)];
-        const bf16_t *kp = k_pages + ((size_t)page * Hkv + h) * PAGE * D + (size_t)(t0 & (PAGE - 1)) * D;
-        const bf16_t *vp = v_pages + ((size_t)page * Hkv + h) * D * PAGE + (t0 & (PAGE - 1));
-        // all loads of the step first: 16 KB of keys, 16 KB of values per wave
-        u32x4 kr[4][4], vr[8][2];
+    // A wave's steps are 256 positions apart, i.e. one page each.  The keys of a step are loaded one step ahead (their
+    // registers are free as soon as the scores are formed), its values at the start of the step: 16 KB of each per wave.
+    u32x4 kr[4][4], vr[8][2];
+    auto page_of = [&](int s) { return block_table[(size_t)b * max_pages + ((tok0 + s * STEP) >> 8)]; };
+    auto load_keys = [&](int s, int page) {
+        const bf16_t *kp = k_pages + ((size_t)page * Hkv + h) * PAGE * D + (size_t)((tok0 + s * STEP) & (PAGE - 1)) * D;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int i = 0; i < 4; ++i) kr[t][i] = ld16(kp + (size_t)(16 * (c >> 2) + 4 * t + (c & 3)) * D + 32 * i + 8 * q);
+    };
+    int page = wave < steps ? page_of(wave) : 0;
+    if (wave < steps) load_keys(wave, page);
+    for (int s = wave; s < steps; s += 4) {
+        const int t0 = tok0 + s * STEP;                                // first position of the step
+        const bf16_t *vp = v_pages + ((size_t)page * Hkv + h) * D * PAGE + (t0 & (PAGE - 1));
 #pragma unroll
         for (int c8 = 0; c8 < 8; ++c8)
 #pragma unroll
             for (int u = 0; u < 2; ++u) vr[c8][u] = ld16(vp + (size_t)(16 * c8 + c) * PAGE + 16 * q + 8 * u);
+        const int page_next = s + 4 < steps ? page_of(s + 4) : 0;
 
         // scores of head c at positions t0 + 16 q + 4 t + j
         f32x4 st[4];
@@ -80,6 +86,8 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
                 st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[t][i]), __builtin_bit_cast(bf16x8, qop[i]),
                                                                 st[t], 0, 0, 0);
         }
+        if (s + 4 < steps) load_keys(s + 4, page_next);                // the key registers are free: next step's keys
+        page = page_next;
         const int left = n - (t0 + 16 * q);                             // valid positions among this lane's 16
         float smax = kNegBig;
 #pragma unroll
