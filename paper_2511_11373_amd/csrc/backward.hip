@@ -29,9 +29,9 @@ hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void
                             int NW, hipStream_t st);
 bool bw_lds_applicable(const moe_shape_t &s);
 hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
-                              const void *list, bf16_t *out, int KD, int N, hipStream_t st);
-hipError_t launch_bw_lds_wgrad(const moe_shape_t &s, const bf16_t *P, const bf16_t *Q, const int32_t *off, float *out, int M, int N,
-                               hipStream_t st);
+                              const void *list, const bf16_t *zeros, bf16_t *out, int KD, int N, hipStream_t st);
+hipError_t launch_bw_lds_wgrad(const moe_shape_t &s, const bf16_t *P, const bf16_t *Q, const int32_t *off, const bf16_t *zeros,
+                               float *out, int M, int N, hipStream_t st);
 hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
 
 namespace {
@@ -206,6 +206,7 @@ struct BwWorkspace {
     bf16_t *x_perm, *up_perm;           // [n][H] each: x and d_out copied into expert-sorted row order
     float *dw_row, *dl;                 // [n] each: <dq, a> per row (later dl per row), dl per assignment
     void *big_list;                     // per-XCD row-tile list of the forward pass's large-batch GEMM
+    bf16_t *zeros;                      // 512 zero bytes: what the large-batch GEMMs read past an expert's last row
     size_t total;
 };
 
@@ -228,6 +229,7 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.dw_row, n * 4);
     take(b.dl, n * 4);
     take(b.big_list, big_tile_list_bytes(s));
+    take(b.zeros, 512);
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
     return b;
 }
@@ -261,6 +263,7 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     const bool fwd_kernel = big_plain_applicable(H, I) && (long)n >= 128L * E;
     const bool lds_kernels = bw_lds_applicable(s);      // large batches: the LDS-pipelined GEMMs
     if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
+    if (lds_kernels) MOE_TRY(zero_floats(reinterpret_cast<float *>(b.zeros), 128, st));
     bw_mark(probe);
     if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wg, g, H, I, st));
     else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
@@ -268,23 +271,23 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wu, b.u, H, I, st));
     else MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.dq, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.zeros, b.dq, H, I, st));
     else MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
     bw_mark(probe);
     hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, b.dg, b.du, wg, wu, b.big_list, dxp, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, b.dg, b.du, wg, wu, b.big_list, b.zeros, dxp, I, H, st));
     else MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, up_rows, b.aw, off, d_wd, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, up_rows, b.aw, off, b.zeros, d_wd, H, I, st));
     else MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.dg, x_rows, off, d_wg, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.dg, x_rows, off, b.zeros, d_wg, I, H, st));
     else MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.du, x_rows, off, d_wu, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.du, x_rows, off, b.zeros, d_wu, I, H, st));
     else MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
     bw_mark(probe);
 #undef MOE_TRY

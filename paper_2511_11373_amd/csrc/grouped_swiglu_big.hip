@@ -103,12 +103,15 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int slot = blockIdx.x >> 3;
     const i32x4 *entry = tile_list + 2 * ((blockIdx.x & 7) * tiles_per_xcd + slot / n_wtiles);
     const i32x4 ea = entry[0], eb = entry[1];
-    const int e = ea[0], row_end = ea[2];
+    // the same in every lane: kept in scalar registers
+    const int e = __builtin_amdgcn_readfirstlane(ea[0]), row_end = __builtin_amdgcn_readfirstlane(ea[2]);
     if (e < 0) return;
-    const int in_run = slot - ea[3] * n_wtiles;                 // ea[3]: first row tile of the run in this XCD's list
-    const int wtile = GATE_UP ? in_run % n_wtiles : in_run / eb[0];      // eb[0]: row tiles in the run
-    const int rt = GATE_UP ? in_run / n_wtiles : in_run % eb[0];
-    const int row0 = ea[1] + (eb[1] + rt) * BT;                 // ea[1]: the expert's first row, eb[1]: the run's first tile in the expert
+    const int run_tiles = __builtin_amdgcn_readfirstlane(eb[0]);                     // row tiles in the run
+    const int in_run = slot - __builtin_amdgcn_readfirstlane(ea[3]) * n_wtiles;      // ea[3]: first row tile of the run in this XCD's list
+    const int wtile = GATE_UP ? in_run % n_wtiles : in_run / run_tiles;
+    const int rt = GATE_UP ? in_run / n_wtiles : in_run % run_tiles;
+    // ea[1]: the expert's first row, eb[1]: the run's first tile in the expert
+    const int row0 = __builtin_amdgcn_readfirstlane(ea[1]) + (__builtin_amdgcn_readfirstlane(eb[1]) + rt) * BT;
     const int wrow0 = wtile * (GATE_UP ? BW / 2 : BW);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -249,74 +252,46 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     else run(FullTile<false>{});
     wait_lds_reads<0>(aop[0], bop[0]);
     MOE_WAIT_VMCNT(0);
-    __builtin_amdgcn_s_barrier();
 
     // ---- epilogue -----------------------------------------------------------------------------------
-    // The accumulators of one 32-token sub-tile go through this wave's 32 KB of LDS (the stage buffers are
-    // free now) and come back with 8 consecutive features of one token per lane, so that results leave as
-    // 16-byte pieces forming 128 (gate/up) or 256 (down) contiguous bytes per token row.
-    unsigned char *region = wave == 0 ? WsA : wave == 1 ? XsA : wave == 2 ? WsB : XsB;
-    constexpr int TROW = 32 * 4 + 16;                    // bytes per token row of a 32x32 float tile (padded)
-    constexpr int TILEB = 32 * TROW;
-    constexpr int LPR = GATE_UP ? 8 : 16;                // lanes per token row on the way out
-    auto wave_sync = [&]() {      // orders this wave's LDS traffic across its lanes (LDS serves a wave in order)
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    auto put_tiles = [&](int b) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
-                *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
-            }
-    };
-    constexpr int NP = 32 * LPR / 64;                    // passes over a sub-tile: 64 / LPR tokens each
-    constexpr int NV = GATE_UP ? 4 : 2;                  // 16-byte LDS reads per pass
-    const int c = lane % LPR;                            // 8-feature piece of this lane
-    const int at = c >> 2, fi = (c & 3) * 8;             // accumulator tile and first feature inside it
-    const int f = wrow0 + (GATE_UP ? ww * 64 : ww * 128) + c * 8;
-    if (nb > 0) put_tiles(0);
+    // Of each 32x32 accumulator tile a lane holds token lane%32 and features 8*rq + 4*(lane/32) .. +3, rq = 0..3.
+    // After rounding to bf16 that is a pair of registers per rq; exchanging the upper half-wave of an even rq's pair
+    // with the lower half-wave of the following odd one's leaves every lane with 8 consecutive features of its
+    // token (lanes 0-31: those of the even rq, lanes 32-63: of the odd one).  Results leave as 16-byte pieces, two
+    // lanes to 32 bytes of a token row, and the stores of a sub-tile complete whole 128-byte lines in L2; neither
+    // LDS nor a barrier is involved.
+    constexpr int NA = GATE_UP ? 2 : 4;                  // output tiles per sub-tile: silu(gate)*up, or the four tiles as they are
+    // the lane index is taken afresh: a value derived from the one above would be kept alive across the main loop, where
+    // no register is free for it
+    const int lane_now = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int tok = lane_now & 31, half = lane_now >> 5;
+    const int fbase = wrow0 + (GATE_UP ? ww * 64 : ww * 128) + 8 * half;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         if (b >= nb) break;
-        wave_sync();
-        // all reads of the sub-tile first (one LDS latency per sub-tile instead of one per pass) ...
-        f32x4 v[NP][NV];
+        const int row = row0 + (2 * b + wt) * 32 + tok;
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const int n = p * (64 / LPR) + lane / LPR;    // token inside the 32-token sub-tile
-            const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
-            v[p][0] = *reinterpret_cast<const f32x4 *>(gp);
-            v[p][1] = *reinterpret_cast<const f32x4 *>(gp + 16);
-            if (GATE_UP) {
-                v[p][2] = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB);
-                v[p][3] = *reinterpret_cast<const f32x4 *>(gp + 2 * TILEB + 16);
-            }
-        }
-        wave_sync();
-        // ... then the next sub-tile's accumulators go in behind them while this one is finished and stored
-        if (b + 1 < nb) put_tiles(b + 1 < 4 ? b + 1 : 3);
+        for (int a = 0; a < NA; ++a) {
+            unsigned d[4][2];
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const int n = p * (64 / LPR) + lane / LPR;
-            const int row = row0 + (2 * b + wt) * 32 + n;
-            u32x4 pk;
-            if (GATE_UP) {
-                pk = u32x4{pack_bf16x2(silu_mul_f(v[p][0][0], v[p][2][0]), silu_mul_f(v[p][0][1], v[p][2][1])),
-                           pack_bf16x2(silu_mul_f(v[p][0][2], v[p][2][2]), silu_mul_f(v[p][0][3], v[p][2][3])),
-                           pack_bf16x2(silu_mul_f(v[p][1][0], v[p][3][0]), silu_mul_f(v[p][1][1], v[p][3][1])),
-                           pack_bf16x2(silu_mul_f(v[p][1][2], v[p][3][2]), silu_mul_f(v[p][1][3], v[p][3][3]))};
-            } else {
-                pk = u32x4{pack_bf16x2(v[p][0][0], v[p][0][1]), pack_bf16x2(v[p][0][2], v[p][0][3]),
-                           pack_bf16x2(v[p][1][0], v[p][1][1]), pack_bf16x2(v[p][1][2], v[p][1][3])};
-            }
-            if (row < row_end && f < NW) {
-                // the down pass streams out far more than the caches hold before it is read again
-                if (GATE_UP) *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
-                else __builtin_nontemporal_store(pk, reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f));
+            for (int rq = 0; rq < 4; ++rq)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int r = 4 * rq + 2 * j;
+                    d[rq][j] = GATE_UP ? pack_bf16x2(silu_mul_f(acc[a][b][r], acc[a + 2][b][r]),
+                                                     silu_mul_f(acc[a][b][r + 1], acc[a + 2][b][r + 1]))
+                                       : pack_bf16x2(acc[a][b][r], acc[a][b][r + 1]);
+                }
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const u32x2 s0 = __builtin_amdgcn_permlane32_swap(d[2 * p][0], d[2 * p + 1][0], false, false);
+                const u32x2 s1 = __builtin_amdgcn_permlane32_swap(d[2 * p][1], d[2 * p + 1][1], false, false);
+                const u32x4 pk = {s0[0], s1[0], s0[1], s1[1]};
+                const int f = fbase + a * 32 + 16 * p;
+                if (row < row_end && f < NW) {
+                    // the down pass streams out far more than the caches hold before it is read again
+                    *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
+                }
             }
         }
     }
