@@ -65,7 +65,8 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
  * call to its kernels.  Unlike the other entry points this one blocks until the call has finished on the device.
  *   stage_ms  host float[MOE_BW_NUM_STAGES] out: elapsed milliseconds of
  *             [0] routing (recomputed)   [1] permutation + copies of x and d_out into expert-sorted rows
- *             [2] row-tile list   [3] g = x Wg^T   [4] u = x Wu^T   [5] dq = d_out Wd   [6] row-wise SwiGLU backward
+ *             [2] row-tile list   [3] g = x Wg^T   [4] u = x Wu^T (nothing when one launch, counted under [3], yields both)
+ *             [5] dq = d_out Wd   [6] row-wise SwiGLU backward
  *             [7] dx rows = dg Wg + du Wu   [8] dWd   [9] dWg   [10] dWu   [11] softmax backward, dx, router gradients
  *             [12] an empty interval (two events back to back): what the measurement itself adds to a stage
  * Same arguments, results and errors as moe_backward otherwise.

@@ -22,16 +22,17 @@ hipError_t launch_bw_rows_kfast(const bf16_t *rows, const bf16_t *w, const int32
 hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1, const int32_t *off,
                                 const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st);
 hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
-bool big_plain_applicable(int KD, int NW);
+bool big_pre_activations_applicable(int H, int I);
 size_t big_tile_list_bytes(const moe_shape_t &s);
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
-hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void *list, const bf16_t *w, bf16_t *out, int KD,
-                            int NW, hipStream_t st);
+hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, const void *list,
+                                      const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st);
 bool bw_lds_applicable(const moe_shape_t &s);
 hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
-                              const void *list, const bf16_t *zeros, bf16_t *out, int KD, int N, hipStream_t st);
+                              const void *list, const bf16_t *zeros, const int32_t *a0_token, bf16_t *out, int KD, int N,
+                              hipStream_t st);
 hipError_t launch_bw_lds_wgrad(const moe_shape_t &s, const bf16_t *P, const bf16_t *Q, const int32_t *off, const bf16_t *zeros,
-                               float *out, int M, int N, hipStream_t st);
+                               const int32_t *p_token, const int32_t *q_token, float *out, int M, int N, hipStream_t st);
 hipError_t launch_build_tile_map(const int32_t *off, int E, int tile_rows, int max_tiles, int32_t *tile_map, hipStream_t st);
 
 namespace {
@@ -131,12 +132,12 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
     }
 }
 
-// Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl_row[r] x_perm[r][h].  Block (e, 512-wide slice
+// Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl_row[r] x_perm[r][h] (x_perm[r] = x[row_token[r]] with a map).  Block (e, 512-wide slice
 // of h), 4 waves: wave w sums rows r0 + w, r0 + w + 4, ... in that order, two rows in flight, and the four partial sums are
 // added in wave order, so the result does not depend on timing.
-__global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x_perm, const float *__restrict__ dl_row,
-                                                              const int32_t *__restrict__ off, float *__restrict__ dwr,
-                                                              float *__restrict__ dbias, int H) {
+__global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x_perm, const int32_t *__restrict__ row_token,
+                                                              const float *__restrict__ dl_row, const int32_t *__restrict__ off,
+                                                              float *__restrict__ dwr, float *__restrict__ dbias, int H) {
     __shared__ float part[4][64][9];
     const int e = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int h0 = blockIdx.y * 512 + lane * 8;
@@ -155,15 +156,17 @@ __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__re
         }
     };
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    // row r of the expert-sorted order is row row_token[r] of the matrix passed when a map is given
+    auto row_of = [&](int r) { return (size_t)(row_token ? row_token[r] : r); };
     int r = r0 + wave;
     for (; r + 4 < r1; r += 8) {
         const float c0 = dl_row[r], c1 = dl_row[r + 4];
-        const u32x4 v0 = live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)r * H + h0) : zero;
-        const u32x4 v1 = live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)(r + 4) * H + h0) : zero;
+        const u32x4 v0 = live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero;
+        const u32x4 v1 = live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r + 4) * H + h0) : zero;
         add(c0, v0);
         add(c1, v1);
     }
-    if (r < r1) add(dl_row[r], live ? *reinterpret_cast<const u32x4 *>(x_perm + (size_t)r * H + h0) : zero);
+    if (r < r1) add(dl_row[r], live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero);
 #pragma unroll
     for (int j = 0; j < 8; ++j) part[wave][lane][j] = acc[j];
     part[wave][lane][8] = bsum;
@@ -178,6 +181,13 @@ __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__re
         }
         if (dbias && blockIdx.y == 0 && lane == 0) dbias[e] = tot[8];
     }
+}
+
+// token of every expert-sorted row
+__global__ __launch_bounds__(256) void bw_row_token_kernel(const int32_t *__restrict__ row_to_assign, int K, int n,
+                                                           int32_t *__restrict__ row_token) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r < n) row_token[r] = row_to_assign[r] / K;
 }
 
 __global__ __launch_bounds__(256) void bw_zero_kernel(float *__restrict__ p, size_t count) {
@@ -207,6 +217,7 @@ struct BwWorkspace {
     float *dw_row, *dl;                 // [n] each: <dq, a> per row (later dl per row), dl per assignment
     void *big_list;                     // per-XCD row-tile list of the forward pass's large-batch GEMM
     bf16_t *zeros;                      // 512 zero bytes: what the large-batch GEMMs read past an expert's last row
+    int32_t *row_token;                 // [n]: the token each expert-sorted row belongs to
     size_t total;
 };
 
@@ -230,6 +241,7 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.dl, n * 4);
     take(b.big_list, big_tile_list_bytes(s));
     take(b.zeros, 512);
+    take(b.row_token, n * 4);
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
     return b;
 }
@@ -246,12 +258,19 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
     return MOE_OK;
 }
 
+// Large batches of a shape that every large-batch GEMM takes: those GEMMs can fetch a row through a map, so the block's
+// backward pass hands them x and d_out as they are instead of copies in expert-sorted order.
+bool rows_through_map(const moe_shape_t &s) {
+    return big_pre_activations_applicable(s.H, s.I) && bw_lds_applicable(s);
+}
+
 // The expert part over expert-sorted rows: x_rows [n][H], up_rows [n][H] = the upstream gradient of each row's y
 // (without the routing weight when topk_w is given: the weight of row r is then topk_w[row_to_assign[r]]).
-hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_to_assign,
-                           const float *topk_w, const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
-                           BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu, float *d_wd, hipStream_t st,
-                           BwProbe *probe = nullptr) {
+// With row_token (only if rows_through_map(s)): expert-sorted row r is row row_token[r] of x_rows and of up_rows.
+hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_token,
+                           const int32_t *row_to_assign, const float *topk_w, const int32_t *off, const bf16_t *wg,
+                           const bf16_t *wu, const bf16_t *wd, BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu,
+                           float *d_wd, hipStream_t st, BwProbe *probe = nullptr) {
     const int n = s.T * s.K, H = s.H, I = s.I, E = s.E;
     const int max_tiles = n / kBwTile + (E < n ? E : n);
     int32_t *tiles = b.fwd.tile_map;
@@ -260,34 +279,33 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
     // the pre-activations are forward-form products: the forward pass's large-batch kernel takes them when the shape allows
-    const bool fwd_kernel = big_plain_applicable(H, I) && (long)n >= 128L * E;
+    const bool fwd_kernel = big_pre_activations_applicable(H, I) && (long)n >= 128L * E;
     const bool lds_kernels = bw_lds_applicable(s);      // large batches: the LDS-pipelined GEMMs
     if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     if (lds_kernels) MOE_TRY(zero_floats(reinterpret_cast<float *>(b.zeros), 128, st));
     bw_mark(probe);
-    if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wg, g, H, I, st));
+    if (fwd_kernel) MOE_TRY(launch_big_pre_activations(s, x_rows, row_token, b.big_list, wg, wu, g, b.u, st));      // both from one launch
     else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
     bw_mark(probe);
-    if (fwd_kernel) MOE_TRY(launch_big_plain(s, x_rows, b.big_list, wu, b.u, H, I, st));
-    else MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
+    if (!fwd_kernel) MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.zeros, b.dq, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.zeros, row_token, b.dq, H, I, st));
     else MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
     bw_mark(probe);
     hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, b.dg, b.du, wg, wu, b.big_list, b.zeros, dxp, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, b.dg, b.du, wg, wu, b.big_list, b.zeros, nullptr, dxp, I, H, st));
     else MOE_TRY(launch_bw_rows_kslow(b.dg, b.du, wg, wu, off, tiles, max_tiles, dxp, I, H, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, up_rows, b.aw, off, b.zeros, d_wd, H, I, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, up_rows, b.aw, off, b.zeros, row_token, nullptr, d_wd, H, I, st));
     else MOE_TRY(launch_bw_wgrad(up_rows, b.aw, off, E, d_wd, H, I, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.dg, x_rows, off, b.zeros, d_wg, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.dg, x_rows, off, b.zeros, nullptr, row_token, d_wg, I, H, st));
     else MOE_TRY(launch_bw_wgrad(b.dg, x_rows, off, E, d_wg, I, H, st));
     bw_mark(probe);
-    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.du, x_rows, off, b.zeros, d_wu, I, H, st));
+    if (lds_kernels) MOE_TRY(launch_bw_lds_wgrad(s, b.du, x_rows, off, b.zeros, nullptr, row_token, d_wu, I, H, st));
     else MOE_TRY(launch_bw_wgrad(b.du, x_rows, off, E, d_wu, I, H, st));
     bw_mark(probe);
 #undef MOE_TRY
@@ -333,7 +351,7 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
             return MOE_ERR_HIP;
         return MOE_OK;
     }
-    return expert_backward(s, (const bf16_t *)x_perm, (const bf16_t *)dy_perm, nullptr, nullptr, expert_offsets,
+    return expert_backward(s, (const bf16_t *)x_perm, (const bf16_t *)dy_perm, nullptr, nullptr, nullptr, expert_offsets,
                            (const bf16_t *)w_gate, (const bf16_t *)w_up, (const bf16_t *)w_down, b, (bf16_t *)d_x_perm,
                            d_w_gate, d_w_up, d_w_down, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -371,12 +389,22 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     bw_mark(probe);
     if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
-    // x and d_out in expert-sorted row order, so that the GEMMs address their rows by plain arithmetic
-    if (launch_gather_rows(s, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
-        launch_gather_rows(s, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess)
+    // Large batches: the GEMMs fetch the rows of x and d_out through a row -> token map (both then stay in the caches
+    // instead of being streamed back K times over).  Otherwise: copies of x and d_out in expert-sorted row order, so
+    // that the small-batch GEMMs address their rows by plain arithmetic.
+    const bool mapped = rows_through_map(s);
+    const bf16_t *x_rows = mapped ? (const bf16_t *)x : b.x_perm, *up_rows = mapped ? (const bf16_t *)d_out : b.up_perm;
+    const int32_t *row_token = mapped ? b.row_token : nullptr;
+    if (mapped) {
+        hipLaunchKernelGGL(bw_row_token_kernel, dim3((s.T * s.K + 255) / 256), dim3(256), 0, hs, w.row_to_assign, s.K, s.T * s.K,
+                           b.row_token);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    } else if (launch_gather_rows(s, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
+               launch_gather_rows(s, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess) {
         return MOE_ERR_HIP;
+    }
     bw_mark(probe);
-    if (expert_backward(s, b.x_perm, b.up_perm, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
+    if (expert_backward(s, x_rows, up_rows, row_token, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
                         (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe) != hipSuccess)
         return MOE_ERR_HIP;
     hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
@@ -384,7 +412,7 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, w.topk_idx, (const bf16_t *)w_router,
                        (bf16_t *)d_x, s.H, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, b.x_perm, b.dw_row, w.expert_offsets,
+    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, x_rows, row_token, b.dw_row, w.expert_offsets,
                        d_w_router, d_router_bias, s.H);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);

@@ -50,12 +50,15 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
 
 // WGRAD = false: out[r][f] = sum over pairs p and k of xa_p[r][k] * w_p[e][k][f]   (rows r of expert e, bf16 out)
 // WGRAD = true : out[e][m][f] = sum over the rows r of expert e of xa_0[r][m] * w_0[r][f]   (float out)
-// zeros: 512 zero bytes.
-template <bool WGRAD, typename OutT>
+// zeros: 512 zero bytes.  x_token (w_token, weight gradients only), when given: row r of xa_0 (w_0) is not stored in
+// expert-sorted order but is row x_token[r] of the matrix passed, e.g. the token a row is a copy of.
+// MAPPED (weight gradients): 0 no map, 1 the rows of xa_0 through x_token, 2 the rows of w_0 through w_token.
+template <bool WGRAD, int MAPPED, typename OutT>
 __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict__ xa0, const bf16_t *__restrict__ xa1,
                                                         const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1,
                                                         const i32x4 *__restrict__ tile_list, int tiles_per_xcd,
                                                         const int32_t *__restrict__ off, const bf16_t *__restrict__ zeros,
+                                                        const int32_t *__restrict__ x_token, const int32_t *__restrict__ w_token,
                                                         OutT *__restrict__ outp, int KD, int XN, int N, int n_xtiles,
                                                         int n_wtiles, int E, int n_rows) {
     __shared__ __attribute__((aligned(1024))) unsigned char WsA[OPB];
@@ -103,9 +106,13 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     // operand's last column is replaced by the last one there is (its products are never stored).
     const int kl0 = 2 * wave + (lane >> 5), pos = lane & 31;
     const int gpiece = pos ^ ((kl0 & 3) << 2);
-    const size_t lane_w = (size_t)kl0 * N + min(wcol0 + gpiece * 8, N - 8);
-    const size_t lane_x = WGRAD ? (size_t)kl0 * XN + min(row0 + gpiece * 8, XN - 8) : 0;
+    const int col_w = min(wcol0 + gpiece * 8, N - 8), col_x = WGRAD ? min(row0 + gpiece * 8, XN - 8) : 0;
     auto stage_k = [&](int s) { return k_begin + (s % per_pair) * BK; };
+    // a weight gradient with one operand addressed through a token map keeps the 8 row numbers of the stage it loads
+    // next in registers; they are fetched one stage before the loads that use them
+    const int32_t *tok_map = MAPPED == 1 ? x_token : w_token;
+    int tk[8];
+    auto load_tokens = [&](int s, int (&t)[8], int i) { t[i] = tok_map[min(stage_k(s) + 8 * i + kl0, n_rows - 1)]; };
     // Operand stored along k (token rows of the data gradients): load i fills LDS rows (4 i + wave) * 8 .. + 8, lane ->
     // (row lane / 8, position lane % 8); rows past the last one there is are clamped (their results are never stored)
     const int lrow = wave * 8 + (lane >> 3);
@@ -116,20 +123,22 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
         for (int i = 0; i < 8; ++i) {
             int xr = row0 + i * 32 + lrow;
             xr = xr < n_rows ? xr : n_rows - 1;
+            if (x_token) xr = x_token[xr];
             xsrc[i] = (size_t)xr * KD + piece * 8;
         }
     }
-    auto issue = [&](int s, unsigned char *Wl, unsigned char *Xl, int j) {
+    auto issue = [&](int s, unsigned char *Wl, unsigned char *Xl, int j, const int (&t)[8]) {
         const int i = j >> 1, k0 = stage_k(s);
         const bool second = s >= per_pair;
+        const int k = k0 + 8 * i + kl0;
         if (!(j & 1)) {
             const bf16_t *base = WGRAD ? w0 : (second ? w1 : w0) + (size_t)e * KD * N;
-            const bf16_t *src = base + (size_t)(k0 + 8 * i) * N + lane_w;
-            if (WGRAD && k0 + 8 * i + kl0 >= k_end) src = zeros + pos * 8;
+            const bf16_t *src = base + (size_t)(MAPPED == 2 ? t[i] : k) * N + col_w;
+            if (WGRAD && k >= k_end) src = zeros + pos * 8;
             __builtin_amdgcn_global_load_lds((gbl_void *)src, (lds_void *)(Wl + (i * 4 + wave) * 1024), 16, 0, 0);
         } else if (WGRAD) {
-            const bf16_t *src = xa0 + (size_t)(k0 + 8 * i) * XN + lane_x;
-            if (k0 + 8 * i + kl0 >= k_end) src = zeros + pos * 8;
+            const bf16_t *src = xa0 + (size_t)(MAPPED == 1 ? t[i] : k) * XN + col_x;
+            if (k >= k_end) src = zeros + pos * 8;
             __builtin_amdgcn_global_load_lds((gbl_void *)src, (lds_void *)(Xl + (i * 4 + wave) * 1024), 16, 0, 0);
         } else {
             const bf16_t *base = second ? xa1 : xa0;
@@ -222,7 +231,8 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aop[set][a]),
                                                                 __builtin_bit_cast(bf16x8, bop[set][b]), acc[a][b], 0, 0, 0);
             if (m < NREAD) read_one(wrd, xrd, ks_rd, set ^ 1, m);
-            if (ks == 3) issue(s_load, Wl, Xl, m);
+            if (ks == 3) issue(s_load, Wl, Xl, m, tk);
+            if (MAPPED && ks == 0 && m < 8) load_tokens(s_load, tk, m);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -230,10 +240,15 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     if (nst > 0) {
         // stages 0 and 1 (the last stage again if there is only one; it is never read) into buffers A and B
         const int s1 = nst > 1 ? 1 : 0;
+        int tk1[8];
+        if (MAPPED) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) issue(0, WsA, XsA, j);
+            for (int i = 0; i < 8; ++i) { load_tokens(0, tk, i); load_tokens(s1, tk1, i); }
+        }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) issue(s1, WsB, XsB, j);
+        for (int j = 0; j < 16; ++j) issue(0, WsA, XsA, j, tk);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) issue(s1, WsB, XsB, j, tk1);
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -310,23 +325,32 @@ bool bw_lds_applicable(const moe_shape_t &s) {
     return s.H % bwl::BK == 0 && s.I % bwl::BK == 0 && (long)s.T * s.K >= 128L * s.E;
 }
 
-// out[r][f] = sum_k a0[r][k] w0[e][k][f] (+ a1, w1), rows expert-sorted; `list` is the forward pass's per-XCD row-tile list
+// out[r][f] = sum_k a0[r][k] w0[e][k][f] (+ a1, w1), rows expert-sorted (row r of a0 and a1 is row a0_token[r] of the matrix
+// passed when a map is given); `list` is the forward pass's per-XCD row-tile list
 hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
-                              const void *list, const bf16_t *zeros, bf16_t *out, int KD, int N, hipStream_t st) {
+                              const void *list, const bf16_t *zeros, const int32_t *a0_token, bf16_t *out, int KD, int N,
+                              hipStream_t st) {
     const int max_tiles = s.T * s.K / bwl::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
     const int nw = (N + bwl::BT - 1) / bwl::BT;
-    hipLaunchKernelGGL((bwl::bw_lds_kernel<false, bf16_t>), dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, a0, a1, w0, w1,
-                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, (const int32_t *)nullptr, zeros, out, KD, 0, N, 0, nw, s.E,
+    hipLaunchKernelGGL((bwl::bw_lds_kernel<false, 0, bf16_t>), dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, a0, a1, w0, w1,
+                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, (const int32_t *)nullptr, zeros, a0_token, (const int32_t *)nullptr, out, KD, 0, N, 0, nw, s.E,
                        s.T * s.K);
     return hipGetLastError();
 }
 
-// out[e][m][f] = sum over the rows r of expert e of P[r][m] Q[r][f]
+// out[e][m][f] = sum over the rows r of expert e of P[r][m] Q[r][f]; at most one of the two through a row map
 hipError_t launch_bw_lds_wgrad(const moe_shape_t &s, const bf16_t *P, const bf16_t *Q, const int32_t *off, const bf16_t *zeros,
-                               float *out, int M, int N, hipStream_t st) {
+                               const int32_t *p_token, const int32_t *q_token, float *out, int M, int N, hipStream_t st) {
     const int tm = (M + bwl::BT - 1) / bwl::BT, tn = (N + bwl::BT - 1) / bwl::BT;
-    hipLaunchKernelGGL((bwl::bw_lds_kernel<true, float>), dim3(8 * ((s.E + 7) / 8) * tm * tn), dim3(256), 0, st, P, (const bf16_t *)nullptr,
-                       Q, (const bf16_t *)nullptr, (const i32x4 *)nullptr, 0, off, zeros, out, 0, M, N, tm, tn, s.E, s.T * s.K);
+    const dim3 grid(8 * ((s.E + 7) / 8) * tm * tn);
+#define MOE_BW_WGRAD(MAPPED)                                                                                                         \
+    hipLaunchKernelGGL((bwl::bw_lds_kernel<true, MAPPED, float>), grid, dim3(256), 0, st, P, (const bf16_t *)nullptr, Q,              \
+                       (const bf16_t *)nullptr, (const i32x4 *)nullptr, 0, off, zeros, p_token, q_token, out, 0, M, N, tm, tn, s.E, \
+                       s.T * s.K)
+    if (p_token) MOE_BW_WGRAD(1);
+    else if (q_token) MOE_BW_WGRAD(2);
+    else MOE_BW_WGRAD(0);
+#undef MOE_BW_WGRAD
     return hipGetLastError();
 }
 

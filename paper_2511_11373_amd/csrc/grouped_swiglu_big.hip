@@ -83,13 +83,19 @@ constexpr bool big_load_two_ahead = MOE_BIG_LOADPLAN == 3;
 // silu(g)*u with the hardware reciprocal (1 ulp): far inside the bf16 rounding that follows
 __device__ __forceinline__ float silu_mul_f(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
 
-template <bool GATE_UP>
+// What a block's 256 weight rows are and what leaves it: 256 rows of one matrix and their products (the down pass, or
+// any plain grouped GEMM); 128 rows of W_gate and the same 128 of W_up and silu(gate)*up; or those rows and both
+// products, each to a matrix of its own (the backward pass recomputes the pre-activations with it).
+enum BigMode { kBigPlain = 0, kBigGateUp = 1, kBigGateUpRaw = 2 };
+
+template <int MODE>
 __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const bf16_t *__restrict__ xrows, const int32_t *__restrict__ row_map, int K_assign,
     const i32x4 *__restrict__ tile_list, int tiles_per_xcd,
-    const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1, bf16_t *__restrict__ outp, int KD, int NW,
-    int n_wtiles, int n_rows) {
+    const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1, bf16_t *__restrict__ outp, bf16_t *__restrict__ outp2,
+    int KD, int NW, int n_wtiles, int n_rows) {
     using namespace big;
+    constexpr bool GATE_UP = MODE != kBigPlain;
     __shared__ __attribute__((aligned(1024))) unsigned char WsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
@@ -260,7 +266,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     // token (lanes 0-31: those of the even rq, lanes 32-63: of the odd one).  Results leave as 16-byte pieces, two
     // lanes to 32 bytes of a token row, and the stores of a sub-tile complete whole 128-byte lines in L2; neither
     // LDS nor a barrier is involved.
-    constexpr int NA = GATE_UP ? 2 : 4;                  // output tiles per sub-tile: silu(gate)*up, or the four tiles as they are
+    constexpr int NA = MODE == kBigGateUp ? 2 : 4;       // output tiles per sub-tile: silu(gate)*up, or the four tiles as they are
     // the lane index is taken afresh: a value derived from the one above would be kept alive across the main loop, where
     // no register is free for it
     const int lane_now = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
@@ -278,20 +284,20 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int r = 4 * rq + 2 * j;
-                    d[rq][j] = GATE_UP ? pack_bf16x2(silu_mul_f(acc[a][b][r], acc[a + 2][b][r]),
-                                                     silu_mul_f(acc[a][b][r + 1], acc[a + 2][b][r + 1]))
-                                       : pack_bf16x2(acc[a][b][r], acc[a][b][r + 1]);
+                    d[rq][j] = MODE == kBigGateUp ? pack_bf16x2(silu_mul_f(acc[a][b][r], acc[a + 2][b][r]),
+                                                                silu_mul_f(acc[a][b][r + 1], acc[a + 2][b][r + 1]))
+                                                  : pack_bf16x2(acc[a][b][r], acc[a][b][r + 1]);
                 }
+            // tiles 2 and 3 of the two-output form are the up products of the features of tiles 0 and 1
+            bf16_t *dst = (MODE == kBigGateUpRaw && a >= 2) ? outp2 : outp;
+            const int fa = MODE == kBigGateUpRaw ? (a & 1) : a;
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
                 const u32x2 s0 = __builtin_amdgcn_permlane32_swap(d[2 * p][0], d[2 * p + 1][0], false, false);
                 const u32x2 s1 = __builtin_amdgcn_permlane32_swap(d[2 * p][1], d[2 * p + 1][1], false, false);
                 const u32x4 pk = {s0[0], s1[0], s0[1], s1[1]};
-                const int f = fbase + a * 32 + 16 * p;
-                if (row < row_end && f < NW) {
-                    // the down pass streams out far more than the caches hold before it is read again
-                    *reinterpret_cast<u32x4 *>(outp + (size_t)row * NW + f) = pk;
-                }
+                const int f = fbase + fa * 32 + 16 * p;
+                if (row < row_end && f < NW) *reinterpret_cast<u32x4 *>(dst + (size_t)row * NW + f) = pk;
             }
         }
     }
@@ -358,19 +364,20 @@ hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows,
     probe_mark(probe);
     const int nw1 = (s.I + BW / 2 - 1) / (BW / 2), nw2 = (s.H + BW - 1) / BW;
     const int n_rows = s.T * s.K;
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<true>, dim3(8 * tiles_per_xcd * nw1), dim3(256), 0, st, x_rows, row_map,
-                       s.K, list, tiles_per_xcd, wg, wu, act, s.H, s.I, nw1, n_rows);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigGateUp>, dim3(8 * tiles_per_xcd * nw1), dim3(256), 0, st, x_rows, row_map,
+                       s.K, list, tiles_per_xcd, wg, wu, act, (bf16_t *)nullptr, s.H, s.I, nw1, n_rows);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     probe_mark(probe);
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(8 * tiles_per_xcd * nw2), dim3(256), 0, st, (const bf16_t *)act,
-                       (const int32_t *)nullptr, 1, list, tiles_per_xcd, wd, wd, y_perm, s.I, s.H, nw2, n_rows);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigPlain>, dim3(8 * tiles_per_xcd * nw2), dim3(256), 0, st, (const bf16_t *)act,
+                       (const int32_t *)nullptr, 1, list, tiles_per_xcd, wd, wd, y_perm, (bf16_t *)nullptr, s.I, s.H, nw2, n_rows);
     return hipGetLastError();
 }
 
-// ---- the second pass's kernel as a plain grouped GEMM: out[r][f] = sum_k rows[r][k] * W[e][f][k] -------------------
-// (used by the backward pass to recompute the expert pre-activations).  Needs whole k tiles and whole weight tiles.
-bool big_plain_applicable(int KD, int NW) { return KD % big::BK == 0 && NW % big::BW == 0; }
+// ---- both expert pre-activations of expert-sorted rows, g = W_gate[e] v and u = W_up[e] v, each to a matrix of its own --------
+// (the backward pass recomputes them with this).  Needs whole k tiles and whole 128-feature weight tiles.  row_token,
+// when given, names the row of `rows` that each expert-sorted row is a copy of.
+bool big_pre_activations_applicable(int H, int I) { return H % big::BK == 0 && I % (big::BW / 2) == 0; }
 
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st) {
     const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
@@ -378,12 +385,12 @@ hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *
     return hipGetLastError();
 }
 
-hipError_t launch_big_plain(const moe_shape_t &s, const bf16_t *rows, const void *list, const bf16_t *w, bf16_t *out, int KD,
-                            int NW, hipStream_t st) {
+hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, const void *list,
+                                      const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st) {
     const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
-    const int nw = NW / big::BW;
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<false>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, (const int32_t *)nullptr, 1,
-                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, w, w, out, KD, NW, nw, s.T * s.K);
+    const int nw = s.I / (big::BW / 2);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigGateUpRaw>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, row_token, 1,
+                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wg, wu, g, u, s.H, s.I, nw, s.T * s.K);
     return hipGetLastError();
 }
 
