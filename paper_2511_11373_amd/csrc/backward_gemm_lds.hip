@@ -273,47 +273,45 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
         }
         wait_lds(aop[0], bop[0]);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
     }
 
-    // ---- epilogue: accumulators through this wave's 32 KB of LDS, out as 8 consecutive outputs of one row per lane ----
-    unsigned char *region = wave == 0 ? WsA : wave == 1 ? XsA : wave == 2 ? WsB : XsB;
-    constexpr int TROW = 32 * 4 + 16, TILEB = 32 * TROW;
-    const int c = lane & 15, at = c >> 2, fi = (c & 3) * 8;
-    const int f = wcol0 + ww * 128 + c * 8;
+    // ---- epilogue: straight from the accumulators ---------------------------------------------------------------
+    // Of each 32x32 tile a lane holds output row lane % 32 (a token row, or a row m of a weight gradient) and columns
+    // 8 rq + 4 (lane / 32) .. + 3, rq = 0..3.  Float results leave as they are, 16 bytes per lane and rq; bf16 results
+    // are paired up first: exchanging the upper half-wave of an even rq's packed pair with the lower half-wave of the
+    // following odd one's leaves every lane with 8 consecutive columns.  Either way the stores of a tile complete whole
+    // 128-byte lines in L2.
+    const int lane_now = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));      // taken afresh: see grouped_swiglu_big.hip
+    const int orow_e = lane_now & 31, half = lane_now >> 5;
     OutT *obase = WGRAD ? outp + (size_t)e * XN * N : outp;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
+        const int row = row0 + (2 * b + wt) * 32 + orow_e;
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a) {
+            const int f0 = wcol0 + ww * 128 + a * 32;
+            if constexpr (sizeof(OutT) == 4) {
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                f32x4 v = {acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
-                *reinterpret_cast<f32x4 *>(region + a * TILEB + (lane & 31) * TROW + (8 * rq + 4 * (lane >> 5)) * 4) = v;
-            }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int f = f0 + 8 * rq + 4 * half;
+                    if (row < row_end && f < N)
+                        *reinterpret_cast<f32x4 *>(obase + (size_t)row * N + f) =
+                            f32x4{acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]};
+                }
+            } else {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const int n = p * 4 + (lane >> 4);                  // row inside the 32-row sub-tile
-            const unsigned char *gp = region + at * TILEB + n * TROW + fi * 4;
-            const f32x4 g0 = *reinterpret_cast<const f32x4 *>(gp), g1 = *reinterpret_cast<const f32x4 *>(gp + 16);
-            const int row = row0 + (2 * b + wt) * 32 + n;
-            if (row < row_end && f < N) {
-                OutT *dst = obase + (size_t)row * N + f;
-                if constexpr (sizeof(OutT) == 4) {
-                    *reinterpret_cast<f32x4 *>(dst) = g0;
-                    *reinterpret_cast<f32x4 *>(dst + 4) = g1;
-                } else {
-                    *reinterpret_cast<u32x4 *>(dst) = u32x4{pack_bf16x2(g0[0], g0[1]), pack_bf16x2(g0[2], g0[3]),
-                                                            pack_bf16x2(g1[0], g1[1]), pack_bf16x2(g1[2], g1[3])};
+                for (int p = 0; p < 2; ++p) {
+                    const int r0 = 8 * p;
+                    const u32x2 s0 = __builtin_amdgcn_permlane32_swap(pack_bf16x2(acc[a][b][r0], acc[a][b][r0 + 1]),
+                                                                      pack_bf16x2(acc[a][b][r0 + 4], acc[a][b][r0 + 5]), false, false);
+                    const u32x2 s1 = __builtin_amdgcn_permlane32_swap(pack_bf16x2(acc[a][b][r0 + 2], acc[a][b][r0 + 3]),
+                                                                      pack_bf16x2(acc[a][b][r0 + 6], acc[a][b][r0 + 7]), false, false);
+                    const int f = f0 + 16 * p + 8 * half;
+                    if (row < row_end && f < N)
+                        *reinterpret_cast<u32x4 *>(obase + (size_t)row * N + f) = u32x4{s0[0], s1[0], s0[1], s1[1]};
                 }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
