@@ -58,6 +58,7 @@ CASES = [
     wl.small_config(600, 256, 4, 2, 256, dtype=wl.BF16, seed=46, sigma_w=0.05),       # pre-activations by the forward pass's large-batch kernel
     wl.small_config(900, 192, 3, 2, 320, dtype=wl.BF16, seed=47, sigma_w=0.05),       # LDS-pipelined GEMMs, no dimension a multiple of 256
     wl.small_config(152, 64, 3, 2, 320, dtype=wl.BF16, seed=48, sigma_w=0.05),        # few experts: bias gradients cancel almost fully
+    wl.small_config(700, 320, 4, 2, 384, dtype=wl.BF16, seed=50, sigma_w=0.05),       # rows of x and d_out through the token map, ragged last tiles in every GEMM
     wl.small_config(14, 512, 128, 2, 264, dtype=wl.BF16, seed=49, sigma_w=0.05),      # fewer assignments than experts
 ]
 
