@@ -184,6 +184,10 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
             default: bop[set][3] = lds_read_b128<192 * ROWB>(xa); break;
         }
     };
+    // A short (ragged) tile skips what only its missing token sub-tiles would use: their loads (token load i fills
+    // sub-tile i) and the operand reads of token sub-tiles this wave does not multiply; a wave left without any reads nothing.
+    auto load_live = [&](int j) { return !(j & 1) || (j >> 1) < nsub; };
+    auto read_live = [&](int q) { return q == 5 ? nb > 1 : q == 6 ? nb > 2 : q == 7 ? nb > 3 : nb > 0; };
     // One 16-wide k step: 16 MFMAs out of operand set ks&1.  A wave is alone on its SIMD, so an instruction
     // that is not an MFMA only comes for free in the shadow of the MFMA issued just before it (the matrix
     // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and this k step's
@@ -203,9 +207,9 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                 for (int a2 = 0; a2 < 4; ++a2)
                     acc[a2][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a2], bop[set][b], acc[a2][b], 0, 0, 0);
             }
-            if (m < 8) read_one(wa, xa, set ^ 1, m);
+            if (m < 8 && (FULL || read_live(m))) read_one(wa, xa, set ^ 1, m);
             const int j = big_load_slot(ks, m);
-            if (j >= 0) issue(Wn, Xn, k_next, j);
+            if (j >= 0 && (FULL || load_live(j))) issue(Wn, Xn, k_next, j);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -222,17 +226,22 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int k_last = KD - BK;
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) issue(WsA, XsA, 0, j);
+    for (int j = 0; j < 16; ++j)
+        if (load_live(j)) issue(WsA, XsA, 0, j);
     if (big_load_two_ahead) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) issue(WsB, XsB, min(BK, k_last), j);
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        for (int j = 0; j < 16; ++j)
+            if (load_live(j)) issue(WsB, XsB, min(BK, k_last), j);
+        // a whole tile has 16 loads per stage in flight; a short one has fewer, how many is not known to the encoding
+        if (nsub == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else MOE_WAIT_VMCNT(0);
     } else {
         MOE_WAIT_VMCNT(0);
     }
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int q = 0; q < 8; ++q) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
+    for (int q = 0; q < 8; ++q)
+        if (read_live(q)) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
     auto run = [&](auto full_c) {
 #pragma unroll 1
         for (int kt = 0; kt < nk; ++kt) {
