@@ -9,13 +9,14 @@
 // 8q .. 8q+7; result register j is D[4q + j][c]), without LDS and without any transposition:
 //   scores, transposed:  S^T = K Q^T.  A = 16 positions of K (rows), B = the group's query heads (columns, zero beyond
 //     the group), 4 MFMAs over the 128 features.  Which position a row stands for is free: row r of tile t is position
-//     16 (r / 4) + 4 t + r % 4 of the step, so that lane (c, q) ends up with the scores of head c at the 16 consecutive
-//     positions 16 q .. 16 q + 15 (tiles t = 0..3, registers j = 0..3).
+//     8 (r / 4) + r % 4 + 4 (t % 2) + 32 (t / 2) of the step, so that lane (c, q) ends up with the scores of head c at
+//     positions 8 q .. 8 q + 7 (tiles 0, 1) and 32 + 8 q .. + 7 (tiles 2, 3; registers j = 0..3 each).
 //   softmax: per lane over its 16 scores, across the four q groups by two shuffles; running maximum per head, sums kept
 //     per lane and added across q at the very end.
-//   output: O = P V.  A = P (row = head c, the lane's own exponentials: positions 16 q + 8 u .. + 7 for MFMA u = 0, 1),
-//     B = V stored feature-major (column = feature 16 c8 + c, the same 8 consecutive positions = one 16-byte load),
-//     8 feature tiles x 2 MFMAs.  The reduction slots of an MFMA may be any positions as long as A and B agree.
+//   output: O = P V.  A = P (row = head c, the lane's own exponentials: positions 32 u + 8 q .. + 7 for MFMA u = 0, 1),
+//     B = V stored feature-major (column = feature 16 c8 + c, the same 8 consecutive positions = one 16-byte load, the
+//     four q groups of a feature reading 64 contiguous bytes), 8 feature tiles x 2 MFMAs.  The reduction slots of an
+//     MFMA may be any positions as long as A and B agree.
 #include "moe_internal.hpp"
 
 #include "attn_decode.h"
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kr[t][i] = ld16(kp + (size_t)(16 * (c >> 2) + 4 * t + (c & 3)) * D + 32 * i + 8 * q);
+            for (int i = 0; i < 4; ++i) kr[t][i] = ld16(kp + (size_t)(8 * (c >> 2) + (c & 3) + 4 * (t & 1) + 32 * (t >> 1)) * D + 32 * i + 8 * q);
     };
     int page = wave < steps ? page_of(wave) : 0;
     if (wave < steps) load_keys(wave, page);
@@ -73,10 +74,10 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
 #pragma unroll
         for (int c8 = 0; c8 < 8; ++c8)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) vr[c8][u] = ld16(vp + (size_t)(16 * c8 + c) * PAGE + 16 * q + 8 * u);
+            for (int u = 0; u < 2; ++u) vr[c8][u] = ld16(vp + (size_t)(16 * c8 + c) * PAGE + 32 * u + 8 * q);
         const int page_next = s + 4 < steps ? page_of(s + 4) : 0;
 
-        // scores of head c at positions t0 + 16 q + 4 t + j
+        // scores of head c at positions t0 + 8 q + j + 4 (t % 2) + 32 (t / 2)
         f32x4 st[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -88,13 +89,13 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
         }
         if (s + 4 < steps) load_keys(s + 4, page_next);                // the key registers are free: next step's keys
         page = page_next;
-        const int left = n - (t0 + 16 * q);                             // valid positions among this lane's 16
+        const int left = n - (t0 + 8 * q);                              // position 8 q + e of the step is valid iff e < left
         float smax = kNegBig;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float v = (4 * t + j < left) ? st[t][j] * scale_log2 : kNegBig;
+                const float v = (j + 4 * (t & 1) + 32 * (t >> 1) < left) ? st[t][j] * scale_log2 : kNegBig;
                 st[t][j] = v;
                 smax = fmaxf(smax, v);
             }
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
             float p[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                p[j] = (4 * t + j < left) ? exp2f(st[t][j] - m_new) : 0.f;
+                p[j] = (j + 4 * (t & 1) + 32 * (t >> 1) < left) ? exp2f(st[t][j] - m_new) : 0.f;
                 psum += p[j];
             }
             pop[t >> 1][2 * (t & 1)] = pack_bf16x2(p[0], p[1]);
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(const bf16_t *__rest
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
-                        const int e = 8 * u + 2 * w;                    // positions e, e + 1 of the lane's 16
+                        const int e = 32 * u + 2 * w;                   // positions 8 q + e, + 1 of the step
                         const unsigned int keep = (e < left ? 0xFFFFu : 0u) | (e + 1 < left ? 0xFFFF0000u : 0u);
                         vr[c8][u][w] &= keep;
                     }
