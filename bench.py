@@ -30,8 +30,8 @@ HBM_BOUND = ("decode64", "decode512")
 TRAFFIC = {
     "decode64": {"source": "grouped_swiglu_stream.hip", "sha256_16": "53f42e84a7f7d1d3",
                  "fetch_kib": 389676.3, "write_kib": 873.6, "fetch_scale": 2.0, "write_scale": 1.0},
-    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "9186b8f1bc0a0a6e",
-                   "fetch_kib": 1346809.5, "write_kib": 196610.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "22f1beab4ae2f4b3",
+                   "fetch_kib": 1352181.3, "write_kib": 196610.4, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 

@@ -279,7 +279,7 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
     // the pre-activations are forward-form products: the forward pass's large-batch kernel takes them when the shape allows
-    const bool fwd_kernel = big_pre_activations_applicable(H, I) && (long)n >= 128L * E;
+    const bool fwd_kernel = big_pre_activations_applicable(H, I);
     const bool lds_kernels = bw_lds_applicable(s);      // large batches: the LDS-pipelined GEMMs
     if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     if (lds_kernels) MOE_TRY(zero_floats(reinterpret_cast<float *>(b.zeros), 128, st));

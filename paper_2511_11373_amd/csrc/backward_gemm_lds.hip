@@ -318,10 +318,10 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
 }  // namespace bwl
 
 // Shapes the LDS kernels take: whole 64-wide reduction tiles for the data gradients (their reduction length is a
-// multiple of 64), row counts that are multiples of 8 (every H and I is), and enough rows per expert to fill tiles.
-bool bw_lds_applicable(const moe_shape_t &s) {
-    return s.H % bwl::BK == 0 && s.I % bwl::BK == 0 && (long)s.T * s.K >= 128L * s.E;
-}
+// multiple of 64) and row counts that are multiples of 8 (every H and I is).  No batch is too small for them: measured
+// at H = 2048, I = 768, 128 experts they beat the LDS-free kernels from 4 tokens on (0.67 against 0.86 ms) - a backward
+// pass streams every weight and writes every gradient whatever the batch, and these kernels stream better.
+bool bw_lds_applicable(const moe_shape_t &s) { return s.H % bwl::BK == 0 && s.I % bwl::BK == 0; }
 
 // out[r][f] = sum_k a0[r][k] w0[e][k][f] (+ a1, w1), rows expert-sorted (row r of a0 and a1 is row a0_token[r] of the matrix
 // passed when a map is given); `list` is the forward pass's per-XCD row-tile list
