@@ -258,7 +258,7 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
     return MOE_OK;
 }
 
-// Large batches of a shape that every large-batch GEMM takes: those GEMMs can fetch a row through a map, so the block's
+// Shapes that every LDS-pipelined GEMM takes: those GEMMs can fetch a row through a map, so the block's
 // backward pass hands them x and d_out as they are instead of copies in expert-sorted order.
 bool rows_through_map(const moe_shape_t &s) {
     return big_pre_activations_applicable(s.H, s.I) && bw_lds_applicable(s);
@@ -280,7 +280,7 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
     // the pre-activations are forward-form products: the forward pass's large-batch kernel takes them when the shape allows
     const bool fwd_kernel = big_pre_activations_applicable(H, I);
-    const bool lds_kernels = bw_lds_applicable(s);      // large batches: the LDS-pipelined GEMMs
+    const bool lds_kernels = bw_lds_applicable(s);      // the LDS-pipelined GEMMs, whenever the shape allows
     if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     if (lds_kernels) MOE_TRY(zero_floats(reinterpret_cast<float *>(b.zeros), 128, st));
     bw_mark(probe);
@@ -389,9 +389,9 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     bw_mark(probe);
     if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
-    // Large batches: the GEMMs fetch the rows of x and d_out through a row -> token map (both then stay in the caches
-    // instead of being streamed back K times over).  Otherwise: copies of x and d_out in expert-sorted row order, so
-    // that the small-batch GEMMs address their rows by plain arithmetic.
+    // Shapes the LDS-pipelined GEMMs take: they fetch the rows of x and d_out through a row -> token map (both then stay
+    // in the caches instead of being streamed back K times over).  Otherwise: copies of x and d_out in expert-sorted row
+    // order, so that the LDS-free GEMMs address their rows by plain arithmetic.
     const bool mapped = rows_through_map(s);
     const bf16_t *x_rows = mapped ? (const bf16_t *)x : b.x_perm, *up_rows = mapped ? (const bf16_t *)d_out : b.up_perm;
     const int32_t *row_token = mapped ? b.row_token : nullptr;

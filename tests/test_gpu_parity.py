@@ -25,6 +25,7 @@ SMALL = [
     wl.small_config(600, 64, 1024, 16, 16, dtype=wl.F32, seed=13, sigma_w=0.1),      # ... with the multi-block permutation (9600 rows)
     wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=10, sigma_w=0.05),   # large batch: matrix-core router, big GEMM off
     wl.small_config(2100, 256, 8, 2, 128, dtype=wl.BF16, seed=11, sigma_w=0.05),   # 525 rows per expert: big GEMM with ragged tiles
+    wl.small_config(420, 256, 8, 2, 128, dtype=wl.BF16, seed=14, sigma_w=0.05),     # ~105 rows per expert: big GEMM, short tiles only
     wl.small_config(260, 256, 16, 2, 128, dtype=wl.BF16, seed=7, renormalize=False, sigma_w=0.05),
 ]
 
