@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const S *__restrict__ y, c
                                                       const float *__restrict__ w, S *__restrict__ out, int T, int H, int K) {
     const int t = blockIdx.x;
     const int h = (blockIdx.y * 256 + threadIdx.x) * 8;
-    if (h >= H) return;
+    if (t >= T || h >= H) return;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int32_t *rows = a2r + (size_t)t * K;
     const float *wk = w + (size_t)t * K;

@@ -231,7 +231,7 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
                                const int32_t *off, const S *wg, const S *wu, const S *wd, bf16_t *act,
                                int32_t *tile_map, S *y_perm, hipStream_t st, Probe *probe, bool tile_map_ready) {
     constexpr int WW = kWW, WT = kWT, MW = kMW, MT = kMT;
-    constexpr int BW = WW * MW * 32, BT = WT * MT * 32;
+    constexpr int BW = WW * MW * 32;
     if constexpr (sizeof(S) == 2) {
         if (stream_gemm_applicable(s)) {
             probe_mark(probe);
