@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
 }
 
 // Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl_row[r] x_perm[r][h] (x_perm[r] = x[row_token[r]] with a map).  Block (e, 512-wide slice
-// of h), 4 waves: wave w sums rows r0 + w, r0 + w + 4, ... in that order, two rows in flight, and the four partial sums are
+// of h), 4 waves: wave w sums rows r0 + w, r0 + w + 4, ... in that order, four rows in flight, and the four partial sums are
 // added in wave order, so the result does not depend on timing.
 __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x_perm, const int32_t *__restrict__ row_token,
                                                               const float *__restrict__ dl_row, const int32_t *__restrict__ off,
@@ -158,15 +158,17 @@ __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__re
     const u32x4 zero = {0u, 0u, 0u, 0u};
     // row r of the expert-sorted order is row row_token[r] of the matrix passed when a map is given
     auto row_of = [&](int r) { return (size_t)(row_token ? row_token[r] : r); };
+    auto row_at = [&](int r) { return live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero; };
     int r = r0 + wave;
-    for (; r + 4 < r1; r += 8) {
-        const float c0 = dl_row[r], c1 = dl_row[r + 4];
-        const u32x4 v0 = live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero;
-        const u32x4 v1 = live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r + 4) * H + h0) : zero;
+    for (; r + 12 < r1; r += 16) {          // four rows in flight per wave: the loop is a chain of memory round trips
+        const float c0 = dl_row[r], c1 = dl_row[r + 4], c2 = dl_row[r + 8], c3 = dl_row[r + 12];
+        const u32x4 v0 = row_at(r), v1 = row_at(r + 4), v2 = row_at(r + 8), v3 = row_at(r + 12);
         add(c0, v0);
         add(c1, v1);
+        add(c2, v2);
+        add(c3, v3);
     }
-    if (r < r1) add(dl_row[r], live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero);
+    for (; r < r1; r += 4) add(dl_row[r], row_at(r));
 #pragma unroll
     for (int j = 0; j < 8; ++j) part[wave][lane][j] = acc[j];
     part[wave][lane][8] = bsum;
