@@ -129,3 +129,29 @@ def test_pipeline_and_segments_shorten_the_time_to_training():
     whole = so.simulate(dict(cfg, segment=1 << 20))
     assert pipe["sum_wait"] / len(pipe["groups"]) < 0.8 * whole["sum_wait"] / len(whole["groups"])
     assert pipe["makespan"] <= whole["makespan"]
+
+
+def test_decode_slots_are_a_hard_limit():
+    # one problem, 8 Solver outputs of exactly L tokens, 3 decode slots, no segmentation: 3 + 3 + 2 -> back at 3 L
+    L = 500
+    cfg = base_cfg(problems=1, capacity=3, segment=1 << 20, short_lo=[L] * 5, short_hi=[L] * 5, long_hi=[L] * 5, p_long=[0] * 5,
+                   p_correct=[ONE, 0, ONE, 0, ONE], p_flag_right=[0] * 5)
+    r = so.simulate(cfg)
+    assert r["groups"][0]["role"] == 0 and r["groups"][0]["t_group"] == 3 * L
+    assert sorted(it["t_done"] for it in r["items"][:8]) == [L] * 3 + [2 * L] * 3 + [3 * L] * 2
+    # the two Verifier groups (16 outputs) follow: 6 more stages of 3, 3, 3, 3, 3, 1
+    assert r["makespan"] == 9 * L
+
+
+def test_a_corrector_starts_from_the_solution_not_from_the_report():
+    # every solution wrong, every error flagged: the Corrector repairs a WRONG solution, so p_correct applies, not p_keep
+    cfg = base_cfg(problems=4, p_correct=[0, 0, ONE, 0, ONE], p_keep=[0] * 5, p_flag_wrong=[0, ONE, 0, ONE, 0], p_flag_right=[0] * 5)
+    r = so.simulate(cfg)
+    c1 = [it for it in r["items"] if it["role"] == 2]
+    assert c1 and all(it["value"] == 1 and it["reward"] == 1 for it in c1)
+    # ... and a RIGHT solution wrongly flagged is kept with p_keep, not repaired with p_correct
+    cfg = base_cfg(problems=4, p_correct=[ONE, 0, 0, 0, 0], p_keep=[0, 0, ONE, 0, ONE], p_flag_wrong=[0, ONE, 0, ONE, 0],
+                   p_flag_right=[0, ONE, 0, ONE, 0])
+    r = so.simulate(cfg)
+    c1 = [it for it in r["items"] if it["role"] == 2]
+    assert c1 and all(it["value"] == 1 for it in c1)
