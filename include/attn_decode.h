@@ -47,8 +47,11 @@ int attn_decode_workspace_bytes(const attn_shape_t *shape, size_t *out_bytes);
 /*
  *   q [B, Hq, D]    k_pages, v_pages as above    block_table [B, max_pages] int32    seq_lens [B] int32
  *   out [B, Hq, D] bf16 out
- * The context is processed in chunks of 2048 positions by separate blocks (running maximum and sum per chunk, float
- * accumulation on the matrix cores) and the chunks are merged in position order, so results do not depend on timing.
+ * All 64-position steps of all (sequence, key/value head) pairs form one list that is cut into equal contiguous shares,
+ * one per resident wave (8 per compute unit of the current device); a wave keeps a running maximum and sum (float
+ * accumulation on the matrix cores) and writes a partial result per pair it touches, and the partial results of a pair
+ * are merged in position order.  The split depends on the lengths and the device only, so results do not depend on
+ * timing.  The workspace holds the step counts and the partial results; its contents mean nothing between calls.
  */
 int attn_decode(const attn_shape_t *shape, const void *q, const void *k_pages, const void *v_pages,
                 const int32_t *block_table, const int32_t *seq_lens, void *out, void *ws, size_t ws_bytes, void *stream);

@@ -73,6 +73,27 @@ def test_decode_attention_against_oracle(lens, Hq, Hkv):
             assert np.all(got[b] == 0.0)
 
 
+def _many_short(seed, B, longest):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(1, longest + 1, B)
+    lens[rng.random(B) < 0.15] = 0
+    return [int(n) for n in lens]
+
+
+@pytest.mark.parametrize("lens,Hq,Hkv", [
+    (_many_short(5, 1000, 192), 4, 4),                 # a wave's share of the steps runs over several sequences, empty ones among them
+    ([150000], 8, 1),                                  # one sequence shared by every wave: over a thousand partial results to merge
+    ([40000, 3, 0, 129, 40000, 64, 0], 8, 2),          # shares that end inside, at the end of and just after a short sequence
+], ids=["many_short", "one_long", "mixed"])
+def test_shares_of_the_step_list(lens, Hq, Hkv):
+    """The split of the work into per-wave shares: the lengths decide where shares begin and end, so these cases put
+    share boundaries in every kind of place."""
+    got, ref = run_case(len(lens) + Hq, lens, Hq, Hkv, poison=True)
+    for b, n in enumerate(lens):
+        if n == 0:
+            assert np.all(got[b] == 0.0)
+
+
 @pytest.mark.parametrize("name", ["attn_small", "attn64"])
 def test_bench_workload_on_sampled_sequences(name):
     """The bench workload in the configuration bench.py times (64 sequences of 34k-96k positions, 8 GB of cache drawn on the
