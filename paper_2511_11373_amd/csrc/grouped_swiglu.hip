@@ -10,6 +10,8 @@
 // sized from an upper bound so the host never reads the offsets.
 #include "moe_internal.hpp"
 
+#include <type_traits>
+
 namespace moe {
 
 // ---- tile list -----------------------------------------------------------------------------
@@ -97,29 +99,31 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ww = wave % WW, wt = wave / WW;
 
-    // staging assignments: chunk c -> (row c/CPR, k piece c%CPR)
-    const SW *wsrc[WPT]; bool wok[WPT]; int wdst[WPT];
+    // staging assignments: chunk c -> (row c/CPR, k piece c%CPR); NT is a multiple of CPR, so a thread stages the same k
+    // piece of every row it has.  Every load of the main loop is unconditional (a load on one path only would make the
+    // compiler wait for all loads in flight where the paths meet): rows that do not exist are replaced by one that does
+    // (their results are never stored), a k piece past the end of the rows re-reads the last one and is zeroed when staged.
+    static_assert(NT % CPR == 0, "a thread stages one k piece");
+    const int kcol = (tid % CPR) * 8;
+    const SW *wsrc[WPT]; int wdst[WPT];
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
-        const int c = tid + i * NT;
-        const int mat = c / (BW * CPR), r = (c / CPR) % BW, kc = c % CPR;
-        const int wr = wrow0 + r;
-        wok[i] = c < WCH && wr < NW;
+        const int c = min(tid + i * NT, WCH - 1);
+        const int mat = c / (BW * CPR), r = (c / CPR) % BW;
+        const int wr = min(wrow0 + r, NW - 1);
         const SW *base = (GATE_UP && mat == 1) ? w1 : w0;
-        wsrc[i] = base + ((size_t)e * NW + (wok[i] ? wr : 0)) * KD + kc * 8;
-        wdst[i] = (mat * BW + r) * LDK + kc * 8;
+        wsrc[i] = base + ((size_t)e * NW + wr) * KD;
+        wdst[i] = (mat * BW + r) * LDK + kcol;
     }
-    const SX *xsrc[XPT]; bool xok[XPT]; int xdst[XPT];
+    const SX *xsrc[XPT]; int xdst[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-        const int c = tid + i * NT;
-        const int r = c / CPR, kc = c % CPR;
-        const int row = row0 + r;
-        xok[i] = c < XCH && row < row_end;
-        int src = xok[i] ? row : row0;
+        const int c = min(tid + i * NT, XCH - 1);
+        const int r = c / CPR;
+        int src = min(row0 + r, row_end - 1);
         if (row_map) src = row_map[src] / K_assign;
-        xsrc[i] = xrows + (size_t)src * KD + kc * 8;
-        xdst[i] = r * LDK + kc * 8;
+        xsrc[i] = xrows + (size_t)src * KD;
+        xdst[i] = r * LDK + kcol;
     }
 
     f32x16 acc[NMAT][MW][MT];
@@ -134,24 +138,27 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
 
     u32x4 wreg[2][WPT], xreg[2][XPT];
     auto fetch = [&](int k0, int set) {
+        const int kk = min(k0 + kcol, KD - 8);
 #pragma unroll
-        for (int i = 0; i < WPT; ++i)
-            wreg[set][i] = load8_bf16(wsrc[i] + k0, wok[i] && (k0 + (tid + i * NT) % CPR * 8) < KD);
+        for (int i = 0; i < WPT; ++i) wreg[set][i] = load8_bf16(wsrc[i] + kk, true);
 #pragma unroll
-        for (int i = 0; i < XPT; ++i)
-            xreg[set][i] = load8_bf16(xsrc[i] + k0, xok[i] && (k0 + (tid + i * NT) % CPR * 8) < KD);
+        for (int i = 0; i < XPT; ++i) xreg[set][i] = load8_bf16(xsrc[i] + kk, true);
     };
     const int arow = lane & 31, akq = (lane >> 5) * 8;
-    auto step = [&](int k0, int set) {      // k tile at k0 is in registers `set`
+    auto step = [&](int k0, int set, auto fetch_tag) __attribute__((always_inline)) {      // k tile at k0 is in registers `set`
         __syncthreads();
+        const bool past = k0 + kcol >= KD;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < WPT; ++i)
-            if (tid + i * NT < WCH) *reinterpret_cast<u32x4 *>(&Ws[wdst[i]]) = wreg[set][i];
+            if (tid + i * NT < WCH) *reinterpret_cast<u32x4 *>(&Ws[wdst[i]]) = past ? zero : wreg[set][i];
 #pragma unroll
         for (int i = 0; i < XPT; ++i)
-            if (tid + i * NT < XCH) *reinterpret_cast<u32x4 *>(&Xs[xdst[i]]) = xreg[set][i];
+            if (tid + i * NT < XCH) *reinterpret_cast<u32x4 *>(&Xs[xdst[i]]) = past ? zero : xreg[set][i];
         __syncthreads();
-        if (k0 + 2 * BK < KD) fetch(k0 + 2 * BK, set);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(fetch_tag)::value) fetch(k0 + 2 * BK, set);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 bop[MT];
@@ -170,11 +177,29 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
                 }
         }
     };
+    // Two k tiles are always in flight in registers.  The last steps, which load nothing, are copies of the loop body of
+    // their own, so that inside the loop the loads are unconditional and the waits count exactly.
+    const std::true_type loads;
+    const std::false_type no_load;
+    const int n_steps = (KD + BK - 1) / BK;
     fetch(0, 0);
-    if (BK < KD) fetch(BK, 1);
-    for (int k0 = 0; k0 < KD; k0 += 2 * BK) {
-        step(k0, 0);
-        if (k0 + BK < KD) step(k0 + BK, 1);
+    if (n_steps == 1) {
+        step(0, 0, no_load);
+    } else {
+        fetch(BK, 1);
+        int i = 0;
+        for (; i + 3 < n_steps; i += 2) {
+            step(i * BK, 0, loads);
+            step((i + 1) * BK, 1, loads);
+        }
+        if (n_steps - i == 3) {
+            step(i * BK, 0, loads);
+            step((i + 1) * BK, 1, no_load);
+            step((i + 2) * BK, 0, no_load);
+        } else {
+            step(i * BK, 0, no_load);
+            step((i + 1) * BK, 1, no_load);
+        }
     }
 
     // epilogue: lane holds token (l%32), features 8*(r/4) + 4*(l/32) + 0..3
