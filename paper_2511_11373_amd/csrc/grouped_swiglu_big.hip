@@ -314,9 +314,9 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 
 bool big_gemm_applicable(const moe_shape_t &s) {
     // whole weight tiles in both passes, whole k tiles, and enough rows per expert: measured at H = 2048, I = 768, 128
-    // experts, this kernel overtakes the 64-row tiled one between 40 and 48 rows per expert on average (its 256-row tiles
+    // experts, this kernel overtakes the 64-row tiled one between 56 and 64 rows per expert on average (its 256-row tiles
     // are mostly short ones there, which cost it little more than the weights they stream)
-    return s.dtype == MOE_BF16 && s.H % big::BW == 0 && s.I % (big::BW / 2) == 0 && (long)s.T * s.K >= 48L * s.E;
+    return s.dtype == MOE_BF16 && s.H % big::BW == 0 && s.I % (big::BW / 2) == 0 && (long)s.T * s.K >= 60L * s.E;
 }
 
 // ---- per-XCD row-tile list ---------------------------------------------------------------------------
