@@ -60,12 +60,12 @@ def run_case(seed, lens, Hq, Hkv, poison=False, scale_q=1.0):
 @pytest.mark.parametrize("lens,Hq,Hkv", [
     ([1, 2, 63, 64, 65], 32, 4),                       # first step only, step boundary
     ([255, 256, 257, 1000], 32, 4),                    # page boundary
-    ([2047, 2048, 2049, 5000], 32, 4),                 # chunk boundary, several chunks
+    ([2047, 2048, 2049, 5000], 32, 4),                 # 2048-position boundary (eight pages)
     ([0, 300, 0, 7], 32, 4),                           # sequences without context give zeros
     ([777, 4100], 8, 8),                               # one query head per key/value head
     ([900, 3333, 12], 16, 1),                          # a full group of 16
     ([1500], 12, 4),                                   # group of 3
-], ids=["steps", "pages", "chunks", "empty", "mha", "group16", "group3"])
+], ids=["steps", "pages", "eight_pages", "empty", "mha", "group16", "group3"])
 def test_decode_attention_against_oracle(lens, Hq, Hkv):
     got, ref = run_case(len(lens) * 100 + Hq, lens, Hq, Hkv)
     for b, n in enumerate(lens):
