@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
             wait_lds(aop[0], bop[0]);
             kstep(2, wcur, xcur, 3, Wl, Xl, s_load);
             wait_lds(aop[1], bop[1]);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), as the builtin: the compiler then knows that the row numbers have arrived too
             __builtin_amdgcn_s_barrier();
             kstep(3, wnxt, xnxt, 0, Wl, Xl, s_load);
         }
