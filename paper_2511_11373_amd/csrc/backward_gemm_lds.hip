@@ -119,13 +119,18 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     const int piece = (lane & 7) ^ ((lrow >> 1) & 7);
     size_t xsrc[8];
     if (!WGRAD) {
+        int xr[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int xr = row0 + i * 32 + lrow;
-            xr = xr < n_rows ? xr : n_rows - 1;
-            if (x_token) xr = x_token[xr];
-            xsrc[i] = (size_t)xr * KD + piece * 8;
+        for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, n_rows - 1);
+        if (x_token) {                                                 // the eight row numbers in one round trip
+            int token[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) token[i] = x_token[xr[i]];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xr[i] = token[i];
         }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xsrc[i] = (size_t)xr[i] * KD + piece * 8;
     }
     auto issue = [&](int s, unsigned char *Wl, unsigned char *Xl, int j, const int (&t)[8]) {
         const int i = j >> 1, k0 = stage_k(s);

@@ -135,18 +135,27 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int lrow = wave * 8 + (lane >> 3);                      // LDS row of pair 0
     const int piece = (lane & 7) ^ ((lrow >> 1) & 7);
     const bf16_t *src[16];
+    // token rows: gathered.  Rows past the expert's end belong to the next expert (or are clamped to the
+    // last row there is): they are multiplied like the others and never stored, and not having to know
+    // the expert's end here lets the gather start one memory round trip earlier.  The eight row numbers are
+    // fetched together, under one test of the map pointer: one round trip, not eight in a row.
+    int xr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, n_rows - 1);
+    if (row_map) {
+        int assignment[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) assignment[i] = row_map[xr[i]];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xr[i] = assignment[i] / K_assign;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         // weights: rows are a fixed stride apart (the launcher guarantees whole weight tiles)
         const bf16_t *wm = GATE_UP && i >= 4 ? w1 : w0;
         const int wr = GATE_UP ? (i & 3) * 32 + lrow : i * 32 + lrow;
         src[2 * i] = wm + ((size_t)e * NW + wrow0 + wr) * KD + piece * 8;
-        // token rows: gathered.  Rows past the expert's end belong to the next expert (or are clamped to the
-        // last row there is): they are multiplied like the others and never stored, and not having to know
-        // the expert's end here lets the gather start one memory round trip earlier.
-        int xr = row0 + i * 32 + lrow;
-        xr = xr < n_rows ? xr : n_rows - 1;
-        src[2 * i + 1] = xrows + (size_t)(row_map ? row_map[xr] / K_assign : xr) * KD + piece * 8;
+        src[2 * i + 1] = xrows + (size_t)xr[i] * KD + piece * 8;
     }
 
     f32x16 acc[4][4];
