@@ -27,13 +27,14 @@ constexpr int kPermChunk = 512;        // assignments handled by one wave of the
 __device__ __forceinline__ float bf16_bits_to_float(unsigned int b) { return __uint_as_float(b << 16); }
 
 // float -> bf16 bits, round to nearest even (inputs are finite).
-__device__ __forceinline__ unsigned int float_to_bf16_bits(float f) {
-    unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+// float -> bf16, round to nearest even: gfx950 converts a pair in one instruction (v_cvt_pk_bf16_f32)
+typedef __attribute__((ext_vector_type(2))) float f32x2_cvt;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_cvt;
 __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
-    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+    const f32x2_cvt v = {lo, hi};
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_cvt));
 }
+__device__ __forceinline__ unsigned int float_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
