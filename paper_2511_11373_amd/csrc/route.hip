@@ -419,7 +419,7 @@ __global__ __launch_bounds__(512) void router_fast_logits_kernel(const bf16_t *_
 // Kernel 2: one wave per token.  Lane l keeps the token's values 8*(l + 64 j) .. +7 as doubles, so a candidate's
 // exact logit costs one load, one widening and one fused multiply-add per element and a wave-wide sum.
 template <int R>
-__global__ __launch_bounds__(256) void router_fast_select_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wr,
+__global__ __launch_bounds__(256, 4) void router_fast_select_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ wr,
                                                                  const float *__restrict__ bias, const float *__restrict__ fast,
                                                                  const float *__restrict__ wn2, int32_t *__restrict__ topk_idx,
                                                                  float *__restrict__ topk_w, int T, int H, int E, int K) {
@@ -427,11 +427,13 @@ __global__ __launch_bounds__(256) void router_fast_select_kernel(const bf16_t *_
     __shared__ __attribute__((aligned(16))) unsigned int keys_all[4][EP];
     __shared__ float sel_all[4][EP];
     __shared__ int cid_all[4][EP];
+    __shared__ float cbias_all[4][EP];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + wave;
     if (t >= T) return;
     unsigned int *ckey = keys_all[wave];     // the candidates' exact-logit bits
     int *cid = cid_all[wave];                // candidate expert ids
+    float *cbias = cbias_all[wave];          // and their biases (read here, not between the row loads of the loop below)
     float *sel = sel_all[wave];              // selected logits by slot
 
     // the token row: pieces lane, lane+64, ... of 8 values (H <= 2048: at most 4 per lane), widened once
@@ -454,16 +456,18 @@ __global__ __launch_bounds__(256) void router_fast_select_kernel(const bf16_t *_
     }
     const float xnorm = sqrtf(wave_sum_f32(xsq)) * 1.0001f;
 
-    float fst[R], rad[R];
+    float fst[R], rad[R], bia[R];
     unsigned int lokey[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
         float f = 0.f, w2 = 0.f;
+        bia[r] = 0.f;
         if (e < E) {
             f = fast[(size_t)t * EP + e];
             w2 = wn2[e];
-            if (bias) f += bias[e];
+            if (bias) bia[r] = bias[e];
+            f += bia[r];
         }
         fst[r] = f;
         rad[r] = kGamma * xnorm * (sqrtf(w2) * 1.0001f) + 4e-7f * (1.0f + fabsf(f));
@@ -478,38 +482,45 @@ __global__ __launch_bounds__(256) void router_fast_select_kernel(const bf16_t *_
     for (int r = 0; r < R; ++r) {
         const bool cand = lane + 64 * r < E && fst[r] + rad[r] >= tau;
         const unsigned long long m = __ballot(cand);
-        if (cand) cid[nc + __popcll(m & below)] = lane + 64 * r;
+        if (cand) {
+            cid[nc + __popcll(m & below)] = lane + 64 * r;
+            cbias[nc + __popcll(m & below)] = bia[r];
+        }
         nc += __popcll(m);
     }
     wave_lds_sync();
     // exact logits of the candidates: the sum in double (products exact), one rounding to float
-    u32x4 wv[4];
-    auto fetch_row = [&](int e) {
+    // The rows of two candidates are in flight at any time (a row comes from L2 in about the time it takes to sum a few).
+    // Every load is unconditional, so that the compiler's waits count exactly: past the last candidate the last row is
+    // fetched again, and a lane whose piece lies beyond H re-reads piece 0, which its zero x values cancel.
+    u32x4 wv[2][4];
+    const int pc_of[4] = {lane < npieces ? lane : 0, lane + 64 < npieces ? lane + 64 : 0, lane + 128 < npieces ? lane + 128 : 0,
+                          lane + 192 < npieces ? lane + 192 : 0};
+    auto fetch_row = [&](u32x4 (&row)[4], int ci) {
+        const int e = cid[min(ci, nc - 1)];                  // K >= 1, so there is at least one candidate
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int pc = lane + 64 * j;
-            wv[j] = u32x4{0u, 0u, 0u, 0u};
-            if (pc < npieces) wv[j] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e * H + pc * 8);
-        }
+        for (int j = 0; j < 4; ++j) row[j] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e * H + pc_of[j] * 8);
     };
-    fetch_row(cid[0]);                                   // K >= 1, so there is at least one candidate
-    for (int ci = 0; ci < nc; ++ci) {
-        const int e = cid[ci];
-        u32x4 cur[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cur[j] = wv[j];
-        if (ci + 1 < nc) fetch_row(cid[ci + 1]);         // the next row travels while this one is summed
+    auto exact_logit = [&](const u32x4 (&row)[4], int ci) {
         double s0 = 0.0, s1 = 0.0;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                s0 = fma(xd[j][2 * i], (double)__uint_as_float(cur[j][i] << 16), s0);
-                s1 = fma(xd[j][2 * i + 1], (double)__uint_as_float(cur[j][i] & 0xFFFF0000u), s1);
+                s0 = fma(xd[j][2 * i], (double)__uint_as_float(row[j][i] << 16), s0);
+                s1 = fma(xd[j][2 * i + 1], (double)__uint_as_float(row[j][i] & 0xFFFF0000u), s1);
             }
         double s = wave_sum_f64(s0 + s1);
-        if (bias) s += (double)bias[e];
+        if (bias) s += (double)cbias[ci];
         if (lane == 0) ckey[ci] = float_order_bits((float)s);
+    };
+    fetch_row(wv[0], 0);
+    fetch_row(wv[1], 1);
+    for (int ci = 0; ci < nc; ci += 2) {
+        exact_logit(wv[0], ci);
+        fetch_row(wv[0], ci + 2);
+        if (ci + 1 < nc) exact_logit(wv[1], ci + 1);
+        fetch_row(wv[1], ci + 3);
     }
     wave_lds_sync();
     // order the candidates: (exact logit descending, expert id ascending); the first K are the selection
