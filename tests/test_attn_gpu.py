@@ -82,9 +82,10 @@ def _many_short(seed, B, longest):
 
 @pytest.mark.parametrize("lens,Hq,Hkv", [
     (_many_short(5, 1000, 192), 4, 4),                 # a wave's share of the steps runs over several sequences, empty ones among them
+    (_many_short(6, 2500, 100), 2, 2),                 # more sequences than the step-counting kernel takes in one pass
     ([150000], 8, 1),                                  # one sequence shared by every wave: over a thousand partial results to merge
     ([40000, 3, 0, 129, 40000, 64, 0], 8, 2),          # shares that end inside, at the end of and just after a short sequence
-], ids=["many_short", "one_long", "mixed"])
+], ids=["many_short", "many_sequences", "one_long", "mixed"])
 def test_shares_of_the_step_list(lens, Hq, Hkv):
     """The split of the work into per-wave shares: the lengths decide where shares begin and end, so these cases put
     share boundaries in every kind of place."""
