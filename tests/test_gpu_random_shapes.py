@@ -17,7 +17,7 @@ import test_backward_gpu as backward_cases
 
 pytestmark = pytest.mark.gpu
 
-N_CASES = 36
+N_CASES = 60
 
 
 def _draw(case: int):
