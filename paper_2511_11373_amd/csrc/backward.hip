@@ -104,47 +104,43 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
                                                     const float *__restrict__ dl, const int32_t *__restrict__ topk_idx,
                                                     const bf16_t *__restrict__ wr, bf16_t *__restrict__ dx, int H, int K) {
     const int t = blockIdx.x;
-    const u32x4 zero = {0u, 0u, 0u, 0u};
     for (int p = threadIdx.x; p < (H >> 3); p += 256) {
         float acc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-        // groups of 8 slots: rows and coefficients first, then the 8 independent row loads, then the sums in k order
+        // groups of 8 slots: row numbers, expert ids and coefficients first, then the 16 row loads (8 of dxp, 8 of Wr)
+        // together, then the sums in k order.  Every load is unconditional: a missing slot reads slot 0's rows and enters
+        // with the factor 0.
         for (int k0 = 0; k0 < K; k0 += 8) {
-            int row[8];
+            int row[8], e[8];
+            float c[8], live[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) row[i] = k0 + i < K ? assign_to_row[(size_t)t * K + k0 + i] : -1;
-            u32x4 v[8];
+            for (int i = 0; i < 8; ++i) {
+                const bool ok = k0 + i < K;
+                const size_t a = (size_t)t * K + (ok ? k0 + i : 0);
+                row[i] = assign_to_row[a];
+                e[i] = topk_idx[a];
+                c[i] = ok ? dl[a] : 0.f;
+                live[i] = ok ? 1.f : 0.f;
+            }
+            u32x4 v[8], r[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = row[i] >= 0 ? *reinterpret_cast<const u32x4 *>(dxp + (size_t)row[i] * H + p * 8) : zero;
+            for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4 *>(dxp + (size_t)row[i] * H + p * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e[i] * H + p * 8);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    acc[2 * j] += __uint_as_float(v[i][j] << 16);             // (adding the zeros of missing slots changes nothing)
-                    acc[2 * j + 1] += __uint_as_float(v[i][j] & 0xFFFF0000u);
+                    acc[2 * j] = fmaf(live[i], __uint_as_float(v[i][j] << 16), acc[2 * j]);
+                    acc[2 * j + 1] = fmaf(live[i], __uint_as_float(v[i][j] & 0xFFFF0000u), acc[2 * j + 1]);
                 }
-        }
-        for (int k0 = 0; k0 < K; k0 += 8) {
-            int e[8];
-            float c[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const bool ok = k0 + i < K;
-                e[i] = ok ? topk_idx[(size_t)t * K + k0 + i] : 0;
-                c[i] = ok ? dl[(size_t)t * K + k0 + i] : 0.f;
-            }
-            u32x4 v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e[i] * H + p * 8);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (k0 + i < K) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        acc[2 * j] = fmaf(c[i], __uint_as_float(v[i][j] << 16), acc[2 * j]);
-                        acc[2 * j + 1] = fmaf(c[i], __uint_as_float(v[i][j] & 0xFFFF0000u), acc[2 * j + 1]);
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    acc[2 * j] = fmaf(c[i], __uint_as_float(r[i][j] << 16), acc[2 * j]);
+                    acc[2 * j + 1] = fmaf(c[i], __uint_as_float(r[i][j] & 0xFFFF0000u), acc[2 * j + 1]);
                 }
         }
         *reinterpret_cast<u32x4 *>(dx + (size_t)t * H + p * 8) =
