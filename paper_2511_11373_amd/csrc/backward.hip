@@ -58,8 +58,7 @@ __global__ __launch_bounds__(256) void bw_swiglu_kernel(const bf16_t *__restrict
     float dot = 0.f;
     for (int p = lane; p < (I >> 3); p += 64) {
         const size_t at = (size_t)r * I + p * 8;
-        const u32x4 gv = *reinterpret_cast<const u32x4 *>(g + at), uv = *reinterpret_cast<const u32x4 *>(u + at),
-                    qv = *reinterpret_cast<const u32x4 *>(dq + at);
+        const u32x4 gv = load_once(g + at), uv = load_once(u + at), qv = load_once(dq + at);      // each read once
         float odg[8], odu[8], oaw[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -125,7 +124,7 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
             }
             u32x4 v[8], r[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4 *>(dxp + (size_t)row[i] * H + p * 8);
+            for (int i = 0; i < 8; ++i) v[i] = load_once(dxp + (size_t)row[i] * H + p * 8);
 #pragma unroll
             for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e[i] * H + p * 8);
 #pragma unroll

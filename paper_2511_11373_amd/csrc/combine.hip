@@ -5,7 +5,7 @@
 namespace moe {
 
 __device__ __forceinline__ void load8f(const bf16_t *p, float (&v)[8]) {
-    const u32x4 r = *reinterpret_cast<const u32x4 *>(p);
+    const u32x4 r = load_once(p);                    // every expert output row is read once
 #pragma unroll
     for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(r[j] << 16); v[2 * j + 1] = __uint_as_float(r[j] & 0xFFFF0000u); }
 }

@@ -57,6 +57,10 @@ __device__ __forceinline__ u32x4 load8_bf16(const float *p, bool ok) {
     }
     return v;
 }
+// weights: eight lanes read one whole line of a row, and at the batch sizes this kernel serves an expert's weights are
+// read by one or two token tiles: non-temporal
+__device__ __forceinline__ u32x4 load8_weights(const bf16_t *p) { return load_once(p); }
+__device__ __forceinline__ u32x4 load8_weights(const float *p) { return load8_bf16(p, true); }
 __device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d) {
     u32x2 v = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
     *reinterpret_cast<u32x2 *>(p) = v;
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(WW * WT * 64) void grouped_gemm_kernel(
     auto fetch = [&](int k0, int set) {
         const int kk = min(k0 + kcol, KD - 8);
 #pragma unroll
-        for (int i = 0; i < WPT; ++i) wreg[set][i] = load8_bf16(wsrc[i] + kk, true);
+        for (int i = 0; i < WPT; ++i) wreg[set][i] = load8_weights(wsrc[i] + kk);
 #pragma unroll
         for (int i = 0; i < XPT; ++i) xreg[set][i] = load8_bf16(xsrc[i] + kk, true);
     };

@@ -80,8 +80,8 @@ __global__ __launch_bounds__(256, 2) void stream_gate_up_kernel(
             const bf16_t *u = wu + wrow_off + (size_t)item * 8 * H;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                wreg[r] = *reinterpret_cast<const u32x4 *>(g + (size_t)r * H);
-                wreg[8 + r] = *reinterpret_cast<const u32x4 *>(u + (size_t)r * H);
+                wreg[r] = load_once(g + (size_t)r * H);
+                wreg[8 + r] = load_once(u + (size_t)r * H);
             }
         };
         auto work = [&](int item) {
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void stream_down_kernel(
             const bf16_t *p = wbase + (size_t)(unit >> 1) * 16 * I + (unit & 1) * 384;
 #pragma unroll
             for (int c = 0; c < 12; ++c)
-                wreg[c] = *reinterpret_cast<const u32x4 *>(p + (size_t)(c / 3) * 4 * I + goff[c % 3]);
+                wreg[c] = load_once(p + (size_t)(c / 3) * 4 * I + goff[c % 3]);
         };
         fetch(0);
 #pragma unroll 1

@@ -11,7 +11,7 @@ namespace moe {
 constexpr float kNegHuge = -3.0e38f;   // stands in for -inf: exp(kNegHuge - x) underflows to 0 and never makes a NaN
 
 __device__ __forceinline__ void unpack8(const bf16_t *p, float (&v)[8]) {
-    const u32x4 r = *reinterpret_cast<const u32x4 *>(p);
+    const u32x4 r = load_once(p);                    // the logits are read once
 #pragma unroll
     for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(r[j] << 16); v[2 * j + 1] = __uint_as_float(r[j] & 0xFFFF0000u); }
 }

@@ -36,6 +36,11 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ unsigned int float_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
 
+// Data that a launch reads once, with load instructions that cover whole 128-byte lines: non-temporal loads.  Plain
+// streaming reads of 8 GB reach 7.0 TB/s with them against 6.2 TB/s without.  Not for loads whose instruction covers
+// part of a line and leaves the rest to a later instruction (the line may be fetched again: measured slower).
+__device__ __forceinline__ u32x4 load_once(const bf16_t *p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)); }
+
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Workspace carving.  Every region starts 256-byte aligned.
