@@ -9,13 +9,19 @@
  *   sequence b, query head j, key/value head h = j / (Hq / Hkv), context length n_b = seq_lens[b]:
  *     s[t] = <q[b,j,:], K_b[t,h,:]> / sqrt(D),  p = softmax(s over t < n_b),  out[b,j,:] = sum_t p[t] V_b[t,h,:]
  *
- * Cache layout (chosen for the hardware: every page of a head is one contiguous 64 KB block that is read exactly once
- * and front to back).  The context of sequence b is cut into pages of 256 positions; page i of the sequence is page
- * block_table[b * max_pages + i] of the pools:
- *   k_pages [n_pages, Hkv, 256, D]   position-major: K[t, h, :] of a page are D contiguous elements
- *   v_pages [n_pages, Hkv, D, 256]   feature-major: V[t0 .. t0+255, h, d] of a page are 256 contiguous elements
- * (the values are stored transposed because their product reduces over positions; appending a token writes D scattered
- * elements, once, against thousands of reads).
+ * Cache layout (chosen for the hardware: every page of a head is one contiguous 64 KB block that is read exactly once,
+ * front to back, by load instructions that each fetch eight whole 128-byte lines).  The context of sequence b is cut
+ * into pages of 256 positions; page i of the sequence is page block_table[b * max_pages + i] of the pools:
+ *   k_pages [n_pages, Hkv, 32768]   v_pages [n_pages, Hkv, 32768]
+ * Inside the 32768 elements of a page and head, each block of 64 positions is 8192 contiguous elements made of 16 tiles
+ * of 512 elements (16 rows of 32 elements).  With p the position inside the block (0..63) and f the feature (0..127):
+ *   K[p, f] is element ((4 t + f / 32) * 16 + r) * 32 + f % 32 of the block,
+ *           where t = 2 (p / 32) + (p % 8) / 4 and r = 4 ((p % 32) / 8) + p % 4;
+ *   V[p, f] is element ((2 (f / 16) + p / 32) * 16 + f % 16) * 32 + p % 32 of the block
+ * (keys: tiles of 16 positions x 32 features; values: tiles of 16 features x 32 positions, i.e. stored transposed, because
+ * their product reduces over positions).  Appending a token writes 4 pieces of 64 bytes of K and 128 single elements of
+ * V, once, against thousands of reads.  paper_2511_11373_amd/workloads.py has the same maps as array reshapes
+ * (attn_tile_keys, attn_tile_values and their inverses).
  *
  * Conventions: all data pointers are DEVICE pointers, 16-byte aligned, bf16 unless stated; the caller owns every buffer
  * and the stream; nothing is allocated or kept; arguments are validated on the host before anything is enqueued.

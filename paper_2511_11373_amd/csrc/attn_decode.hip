@@ -1,5 +1,5 @@
 // Single-token grouped-query attention over a paged key/value cache (bf16, head size 128): HBM-bound, every byte of the
-// cache is read once, in 64 KB pages that are contiguous per head.
+// cache is read once, in 64 KB pages that are contiguous per head and tiled for the load instructions below.
 //
 // The work is the list of all 64-position steps of all (sequence, key/value head) pairs, in that order; it is cut into
 // equal contiguous shares, one per wave, as many waves as the chip holds at once (8 per CU: the registers of a step's keys
@@ -20,6 +20,10 @@
 //     B = V stored feature-major (column = feature 16 c8 + c, the same 8 consecutive positions = one 16-byte load, the
 //     four q groups of a feature reading 64 contiguous bytes), 8 feature tiles x 2 MFMAs.  The reduction slots of an
 //     MFMA may be any positions as long as A and B agree.
+// Storage inside a page of one head (32768 elements), in blocks of 64 positions (8192 elements each):
+//   keys:   tile (t, i) = 512 elements at (4 t + i) * 512: row r of score tile t (the position given above), features
+//           32 i .. + 31, rows 32 elements apart;
+//   values: tile (c8, u) = 512 elements at (2 c8 + u) * 512: feature 16 c8 + c in row c, positions 32 u .. + 31 of the block.
 #include "moe_internal.hpp"
 
 #include <type_traits>
@@ -109,19 +113,21 @@ __global__ __launch_bounds__(256, 2) void attn_stream_kernel(const bf16_t *__res
         }
     };
     auto page_of = [&](int b, int s) { return uniform(block_table[(size_t)b * max_pages + (s >> 2)]); };
+    // Both caches are stored in 1 KB tiles of 16 rows x 64 bytes, exactly what one load instruction of a wave reads (lane
+    // (c, q): row c, bytes 16 q .. + 15), so every instruction reads eight whole 128-byte lines and can be non-temporal.
     auto load_keys = [&](int page, int h, int s) {
-        const bf16_t *kp = k_pages + ((size_t)page * Hkv + h) * PAGE * D + (size_t)((s & 3) * STEP) * D;
+        const bf16_t *kp = k_pages + ((size_t)page * Hkv + h) * PAGE * D + (size_t)(s & 3) * STEP * D + c * 32 + 8 * q;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kr[t][i] = ld16(kp + (size_t)(8 * (c >> 2) + (c & 3) + 4 * (t & 1) + 32 * (t >> 1)) * D + 32 * i + 8 * q);
+            for (int i = 0; i < 4; ++i) kr[t][i] = load_once(kp + (t * 4 + i) * 512);      // tile (t, i): rows of tile t, features 32 i .. + 31
     };
     auto load_values = [&](int page, int h, int s) {
-        const bf16_t *vp = v_pages + ((size_t)page * Hkv + h) * D * PAGE + (s & 3) * STEP;
+        const bf16_t *vp = v_pages + ((size_t)page * Hkv + h) * D * PAGE + (size_t)(s & 3) * STEP * D + c * 32 + 8 * q;
 #pragma unroll
         for (int c8 = 0; c8 < 8; ++c8)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) vr[c8][u] = ld16(vp + (size_t)(16 * c8 + c) * PAGE + 32 * u + 8 * q);
+            for (int u = 0; u < 2; ++u) vr[c8][u] = load_once(vp + (c8 * 2 + u) * 512);      // tile (c8, u): features 16 c8 .. + 15, positions 32 u .. + 31
     };
 
     float m = kNegBig, lsum = 0.f;                 // of head c; lsum covers this lane's positions only

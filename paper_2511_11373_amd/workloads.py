@@ -285,8 +285,9 @@ def attn_lengths_and_table(cfg: AttnConfig):
 
 
 def attn_device_inputs(cfg: AttnConfig, n_pages: int):
-    """q [B, Hq, D], k_pages [n_pages, Hkv, page, D], v_pages [n_pages, Hkv, D, page]: standard normal bf16 drawn on the
-    device with torch's seeded generator (the full-size cache is several GB), 1024 pages at a time."""
+    """q [B, Hq, D], k_pages [n_pages, Hkv, page, D], v_pages [n_pages, Hkv, D, page] (pages in storage order: what was
+    drawn is whatever attn_untile_keys / attn_untile_values make of them): standard normal bf16 drawn on the device with
+    torch's seeded generator (the full-size cache is several GB), 1024 pages at a time."""
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(cfg.seed)
@@ -300,11 +301,55 @@ def attn_device_inputs(cfg: AttnConfig, n_pages: int):
     return q, k_pages, v_pages
 
 
+# Storage order inside a cache page of one head (256 positions x 128 features), as include/attn_decode.h defines it: blocks
+# of 64 positions; a block of keys is 16 tiles (t, i) of 16 rows x 32 features, row r of tile t being position
+# 32 (t / 2) + 8 (r / 4) + 4 (t % 2) + r % 4 of the block; a block of values is 16 tiles (c8, u) of 16 features x 32
+# positions.  These helpers only move elements (any array type with reshape / transpose: numpy or torch).
+def _transpose(a, axes):
+    return a.transpose(*axes) if isinstance(a, np.ndarray) else a.permute(*axes)
+
+
+def attn_tile_keys(k):
+    """[..., 256, 128] position-major -> the page's storage order, same shape."""
+    lead = tuple(k.shape[:-2])
+    n = len(lead)
+    x = k.reshape(lead + (4, 2, 4, 2, 4, 4, 32))          # block, p/32, (p%32)/8, (p%8)/4, p%4, f/32, f%32
+    x = _transpose(x, tuple(range(n)) + tuple(n + i for i in (0, 1, 3, 5, 2, 4, 6)))     # block, t = (p/32, (p%8)/4), i, r = ((p%32)/8, p%4), f%32
+    return x.reshape(lead + (256, 128))
+
+
+def attn_untile_keys(k):
+    """Inverse of attn_tile_keys."""
+    lead = tuple(k.shape[:-2])
+    n = len(lead)
+    x = k.reshape(lead + (4, 2, 2, 4, 4, 4, 32))
+    x = _transpose(x, tuple(range(n)) + tuple(n + i for i in (0, 1, 4, 2, 5, 3, 6)))
+    return x.reshape(lead + (256, 128))
+
+
+def attn_tile_values(v):
+    """[..., 128, 256] feature-major -> the page's storage order, same shape."""
+    lead = tuple(v.shape[:-2])
+    n = len(lead)
+    x = v.reshape(lead + (8, 16, 4, 2, 32))               # f/16, f%16, block, (p%64)/32, p%32
+    x = _transpose(x, tuple(range(n)) + tuple(n + i for i in (2, 0, 3, 1, 4)))
+    return x.reshape(lead + (128, 256))
+
+
+def attn_untile_values(v):
+    """Inverse of attn_tile_values."""
+    lead = tuple(v.shape[:-2])
+    n = len(lead)
+    x = v.reshape(lead + (4, 8, 2, 16, 32))
+    x = _transpose(x, tuple(range(n)) + tuple(n + i for i in (1, 3, 0, 2, 4)))
+    return x.reshape(lead + (128, 256))
+
+
 def attn_sequence_to_host(cfg: AttnConfig, k_pages, v_pages, table, lens, b: int):
     """The logical cache of sequence b as float arrays k, v [n, Hkv, D] (copied back from the device pools)."""
     import torch
     n = int(lens[b])
     pg = torch.from_numpy(table[b, :(n + cfg.page - 1) // cfg.page].astype(np.int64)).to(k_pages.device)
-    k = k_pages[pg].permute(0, 2, 1, 3).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
-    v = v_pages[pg].permute(0, 3, 1, 2).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
+    k = attn_untile_keys(k_pages[pg]).permute(0, 2, 1, 3).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
+    v = attn_untile_values(v_pages[pg]).permute(0, 3, 1, 2).reshape(-1, cfg.Hkv, cfg.D)[:n].float().cpu().numpy()
     return k, v

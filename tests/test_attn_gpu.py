@@ -36,7 +36,7 @@ def paged(rng, lens, Hkv, k, v, extra_pages=3, poison=False):
             m = min(PAGE, int(n) - i * PAGE)
             kp[pid, :, :m, :] = k[b, i * PAGE:i * PAGE + m].transpose(1, 0, 2)
             vp[pid, :, :, :m] = v[b, i * PAGE:i * PAGE + m].transpose(1, 2, 0)
-    return kp, vp, table, max_pages, n_pages
+    return wl.attn_tile_keys(kp), wl.attn_tile_values(vp), table, max_pages, n_pages        # the pages' storage order
 
 
 def run_case(seed, lens, Hq, Hkv, poison=False, scale_q=1.0):
