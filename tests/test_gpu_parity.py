@@ -161,6 +161,23 @@ def test_grouped_gemm_uneven_experts(lib, oracle_lib):
     check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
 
 
+def test_streaming_gemm_uneven_experts(lib, oracle_lib):
+    """The decode-sized (weight-streaming) kernels on hand-made expert segments at the shape they are built for: experts
+    without rows, with one row, with exactly 16, and with 17 and 33 rows (two and three passes of 16 tokens)."""
+    counts = [0, 1, 17, 0, 16, 33, 5, 0, 2]
+    n, H, I, E = sum(counts), 2048, 768, len(counts)
+    assert n <= 12 * E                                       # the batch size up to which these kernels are selected
+    cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=32, sigma_w=0.02)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    y = moe.moe_grouped_swiglu(shp, g["x"], torch.from_numpy(off).cuda(), g["w_gate"], g["w_up"], g["w_down"], ws)
+    o_y = oracle_lib.grouped_swiglu(d["x_f32"], off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
+    check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
+
+
 def test_empty_batch_and_bad_arguments(lib):
     shp = moe.make_shape(0, 64, 4, 2, 32, moe.MOE_BF16)
     ws = moe.alloc_workspace(shp)
