@@ -30,6 +30,10 @@ HBM_BOUND = ("decode64", "decode512")
 TRAFFIC = {
     "decode64": {"source": "grouped_swiglu_stream.hip", "sha256_16": "5de0e597a26c419a",
                  "fetch_kib": 385068.4, "write_kib": 778.5, "fetch_scale": 2.0, "write_scale": 1.0},
+    "attn64": {"source": "attn_decode.hip", "sha256_16": "e8bc56f296527f59",
+               "fetch_kib": 4023095.8, "write_kib": 9335.4, "fetch_scale": 2.0, "write_scale": 1.0},
+    "logprob16k": {"source": "grpo.hip", "sha256_16": "1d6b06c37e215813",
+                   "fetch_kib": 2432523.5, "write_kib": 515.8, "fetch_scale": 2.0, "write_scale": 1.0},
     "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "0a768b124520a545",
                    "fetch_kib": 1353896.0, "write_kib": 196610.3, "fetch_scale": 2.0, "write_scale": 1.0},
 }
@@ -132,7 +136,7 @@ def bench_logprob(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": cfg.N, "vocab": cfg.V, "responses": cfg.G, "logits_dtype": "bf16"},
         "roofline": {"bound": "hbm", "kernel": "logprob_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic("logprob16k"),
                      "bytes_per_launch": int(nbytes), "avg_launch_ms": round(k_ms, 5)},
         "cpu_baseline": cpu,
         "objective": float(out[4].item()),
@@ -279,7 +283,8 @@ def bench_attn(args):
         "config": {"workload": "attn64", "sequences": B, "query_heads": Hq, "kv_heads": Hkv, "head_size": D,
                    "context_min": int(lens.min()), "context_mean": int(lens.mean()), "context_max": int(lens.max()), "cache_GB": round(nbytes / 1e9, 2)},
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": nbytes, "avg_launch_ms": round(k_ms, 5)},
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic("attn64"), "bytes_per_launch": nbytes,
+                     "avg_launch_ms": round(k_ms, 5)},
         "cpu_baseline": cpu}))
 
 
