@@ -20,7 +20,9 @@
  * Restrictions of this pass: shape->dtype must be MOE_BF16 (else MOE_ERR_DTYPE) and shape->renormalize must be
  * nonzero (else MOE_ERR_SHAPE).  x, the weights, d_out, d_x and the row gradients are bf16; every weight
  * gradient is float and is written, not accumulated into (an expert that received no row gets zeros).
- * Nothing is kept from a forward call: routing, permutation and the expert pre-activations are recomputed.
+ * Nothing is kept from a forward call: routing, permutation and the expert pre-activations are recomputed (what
+ * activation recomputation does for long sequences).  The pair moe_forward_saving / moe_backward_saved is the other
+ * choice: the forward pass keeps the pre-activations g and u of every expert-sorted row, the backward pass reads them.
  * Intermediates are rounded to bf16, sums run in float on the matrix cores.
  */
 #ifndef MOE_FFN_BACKWARD_H
@@ -59,6 +61,32 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
                           const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
                           void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
                           float *d_w_down, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * moe_forward that also keeps what the backward pass would otherwise recompute (Section 4.1: every rollout token is
+ * trained on, so each forward pass of training is followed by its backward pass).
+ *   x, w_router, router_bias, w_gate, w_up, w_down, out: as for moe_forward
+ *   g_rows, u_rows [T*K, I] bf16 out: g = W_gate[e] x_t and u = W_up[e] x_t of expert-sorted row r (the row order of
+ *                                     moe_permute; a pure function of the routing, so moe_backward_saved finds it again)
+ *   ws: a forward workspace (the size that moe_workspace_bytes gives for `shape`)
+ * The activations are formed from the rounded g and u (one rounding more than in moe_forward: same tolerance).
+ * Restrictions: MOE_BF16 (else MOE_ERR_DTYPE); H a multiple of 256 and I a multiple of 128 (else MOE_ERR_SHAPE): the
+ * large-batch kernels do all the work, whatever T is.
+ */
+moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                const void *w_gate, const void *w_up, const void *w_down, void *out, void *g_rows,
+                                void *u_rows, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * moe_backward with the pre-activations supplied instead of recomputed.
+ *   g_rows, u_rows [T*K, I] bf16: as written by moe_forward_saving for the same x, router and expert weights
+ * Everything else as for moe_backward (same workspace size, same results: with g_rows and u_rows from
+ * moe_forward_saving the gradients are bit for bit those of moe_backward, whose recomputation yields the same g and u).
+ */
+moe_status_t moe_backward_saved(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                const void *g_rows, const void *u_rows, void *d_x, float *d_w_router, float *d_router_bias,
+                                float *d_w_gate, float *d_w_up, float *d_w_down, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * moe_backward with a HIP event recorded on `stream` at every stage boundary, for attributing the time of one

@@ -55,6 +55,30 @@ static moe_status_t check_ws(const moe_shape_t &s, const void *ws, size_t ws_byt
     return MOE_OK;
 }
 
+// act = silu(g) u over whole expert-sorted rows, 8 elements per thread (the forward pass that keeps g and u)
+__global__ __launch_bounds__(256) void swiglu_rows_kernel(const bf16_t *__restrict__ g, const bf16_t *__restrict__ u,
+                                                          bf16_t *__restrict__ act, size_t n8) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const u32x4 gv = *reinterpret_cast<const u32x4 *>(g + i * 8), uv = *reinterpret_cast<const u32x4 *>(u + i * 8);
+    u32x4 av;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float g0 = __uint_as_float(gv[j] << 16), g1 = __uint_as_float(gv[j] & 0xFFFF0000u);
+        const float u0 = __uint_as_float(uv[j] << 16), u1 = __uint_as_float(uv[j] & 0xFFFF0000u);
+        av[j] = pack_bf16x2(g0 / (1.0f + __expf(-g0)) * u0, g1 / (1.0f + __expf(-g1)) * u1);
+    }
+    *reinterpret_cast<u32x4 *>(act + i * 8) = av;
+}
+
+bool big_pre_activations_applicable(int H, int I);
+bool big_down_applicable(int H, int I);
+hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
+hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, int row_div,
+                                      const void *list, const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st);
+hipError_t launch_big_down(const moe_shape_t &s, const bf16_t *act, const void *list, const bf16_t *wd, bf16_t *y_perm,
+                           hipStream_t st);
+
 }  // namespace moe
 
 using namespace moe;
@@ -189,6 +213,40 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
                          void *ws, size_t ws_bytes, void *stream) {
     return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out, ws,
                         ws_bytes, stream, nullptr);
+}
+
+moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                const void *w_gate, const void *w_up, const void *w_down, void *out, void *g_rows,
+                                void *u_rows, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (!big_pre_activations_applicable(shape->H, shape->I) || !big_down_applicable(shape->H, shape->I)) return MOE_ERR_SHAPE;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !out || !g_rows || !u_rows) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
+        misaligned(w_down) || misaligned(out) || misaligned(g_rows) || misaligned(u_rows))
+        return MOE_ERR_ALIGN;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    const moe_shape_t &s = *shape;
+    Workspace w = carve_workspace(s, ws);
+    hipStream_t hs = (hipStream_t)stream;
+    if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs, nullptr) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs, 0, 0, w.tile_map) !=
+        hipSuccess)
+        return MOE_ERR_HIP;
+    if (launch_big_tile_list(s, w.expert_offsets, w.tile_map, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_big_pre_activations(s, (const bf16_t *)x, w.row_to_assign, s.K, w.tile_map, (const bf16_t *)w_gate,
+                                   (const bf16_t *)w_up, (bf16_t *)g_rows, (bf16_t *)u_rows, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    const size_t n8 = (size_t)s.T * s.K * s.I / 8;
+    hipLaunchKernelGGL(swiglu_rows_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, hs, (const bf16_t *)g_rows,
+                       (const bf16_t *)u_rows, w.act, n8);
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    if (launch_big_down(s, w.act, w.tile_map, (const bf16_t *)w_down, (bf16_t *)w.y_perm, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_combine(s, w.y_perm, w.assign_to_row, w.topk_w, out, hs) != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
 }
 
 moe_status_t moe_forward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router,

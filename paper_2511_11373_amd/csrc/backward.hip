@@ -25,8 +25,8 @@ hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off,
 bool big_pre_activations_applicable(int H, int I);
 size_t big_tile_list_bytes(const moe_shape_t &s);
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
-hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, const void *list,
-                                      const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st);
+hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, int row_div,
+                                      const void *list, const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st);
 bool bw_lds_applicable(const moe_shape_t &s);
 hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
                               const void *list, const bf16_t *zeros, const int32_t *a0_token, bf16_t *out, int KD, int N,
@@ -287,11 +287,15 @@ bool rows_through_map(const moe_shape_t &s) {
 hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf16_t *up_rows, const int32_t *row_token,
                            const int32_t *row_to_assign, const float *topk_w, const int32_t *off, const bf16_t *wg,
                            const bf16_t *wu, const bf16_t *wd, BwWorkspace &b, bf16_t *dxp, float *d_wg, float *d_wu,
-                           float *d_wd, hipStream_t st, BwProbe *probe = nullptr) {
+                           float *d_wd, hipStream_t st, BwProbe *probe = nullptr, const bf16_t *g_saved = nullptr,
+                           const bf16_t *u_saved = nullptr) {
     const int n = s.T * s.K, H = s.H, I = s.I, E = s.E;
     const int max_tiles = n / kBwTile + (E < n ? E : n);
     int32_t *tiles = b.fwd.tile_map;
-    bf16_t *g = b.fwd.act;
+    // the pre-activations: the caller's (kept from the forward pass), or recomputed into the workspace
+    const bool saved = g_saved && u_saved;
+    bf16_t *g_new = b.fwd.act;
+    const bf16_t *g = saved ? g_saved : g_new, *u = saved ? u_saved : b.u;
     hipError_t err;
 #define MOE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
     MOE_TRY(launch_build_tile_map(off, E, kBwTile, max_tiles, tiles, st));
@@ -301,15 +305,17 @@ hipError_t expert_backward(const moe_shape_t &s, const bf16_t *x_rows, const bf1
     if (fwd_kernel || lds_kernels) MOE_TRY(launch_big_tile_list(s, off, b.big_list, st));
     if (lds_kernels) MOE_TRY(zero_floats(reinterpret_cast<float *>(b.zeros), 128, st));
     bw_mark(probe);
-    if (fwd_kernel) MOE_TRY(launch_big_pre_activations(s, x_rows, row_token, b.big_list, wg, wu, g, b.u, st));      // both from one launch
-    else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g, H, I, st));
+    if (!saved) {
+        if (fwd_kernel) MOE_TRY(launch_big_pre_activations(s, x_rows, row_token, 1, b.big_list, wg, wu, g_new, b.u, st));      // both from one launch
+        else MOE_TRY(launch_bw_rows_kfast(x_rows, wg, off, tiles, max_tiles, g_new, H, I, st));
+    }
     bw_mark(probe);
-    if (!fwd_kernel) MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
+    if (!saved && !fwd_kernel) MOE_TRY(launch_bw_rows_kfast(x_rows, wu, off, tiles, max_tiles, b.u, H, I, st));
     bw_mark(probe);
     if (lds_kernels) MOE_TRY(launch_bw_lds_rows(s, up_rows, nullptr, wd, nullptr, b.big_list, b.zeros, row_token, b.dq, H, I, st));
     else MOE_TRY(launch_bw_rows_kslow(up_rows, nullptr, wd, nullptr, off, tiles, max_tiles, b.dq, H, I, st));
     bw_mark(probe);
-    hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, b.u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
+    hipLaunchKernelGGL(bw_swiglu_kernel, dim3((n + 3) / 4), dim3(256), 0, st, g, u, b.dq, topk_w, row_to_assign, b.dg, b.du, b.aw,
                        b.dw_row, n, I);
     MOE_TRY(hipGetLastError());
     bw_mark(probe);
@@ -376,11 +382,13 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
 static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
                                   const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
                                   void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
-                                  float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe) {
+                                  float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe,
+                                  const void *g_rows = nullptr, const void *u_rows = nullptr) {
     moe_status_t st = check_bw_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !d_out || !d_x || !d_w_router || !d_w_gate || !d_w_up || !d_w_down)
         return MOE_ERR_NULL;
+    if (misaligned(g_rows) || misaligned(u_rows)) return MOE_ERR_ALIGN;
     if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
         misaligned(w_down) || misaligned(d_out) || misaligned(d_x) || misaligned(d_w_router) || misaligned(d_router_bias) ||
         misaligned(d_w_gate) || misaligned(d_w_up) || misaligned(d_w_down))
@@ -422,7 +430,8 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     }
     bw_mark(probe);
     if (expert_backward(s, x_rows, up_rows, row_token, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
-                        (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe) != hipSuccess)
+                        (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe,
+                        (const bf16_t *)g_rows, (const bf16_t *)u_rows) != hipSuccess)
         return MOE_ERR_HIP;
     hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
@@ -443,6 +452,15 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
                           float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
     return backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias, d_w_gate,
                          d_w_up, d_w_down, ws, ws_bytes, stream, nullptr);
+}
+
+moe_status_t moe_backward_saved(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                const void *g_rows, const void *u_rows, void *d_x, float *d_w_router, float *d_router_bias,
+                                float *d_w_gate, float *d_w_up, float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
+    if (!g_rows || !u_rows) return MOE_ERR_NULL;
+    return backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias, d_w_gate,
+                         d_w_up, d_w_down, ws, ws_bytes, stream, nullptr, g_rows, u_rows);
 }
 
 moe_status_t moe_backward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,

@@ -405,12 +405,27 @@ hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *
     return hipGetLastError();
 }
 
-hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, const void *list,
-                                      const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st) {
+// (row_div: expert-sorted row r is row row_token[r] / row_div of `rows`: 1 for a row -> token map, K for the forward
+// pass's row -> assignment map)
+hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, int row_div,
+                                      const void *list, const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st) {
     const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
     const int nw = s.I / (big::BW / 2);
-    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigGateUpRaw>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, row_token, 1,
-                       reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wg, wu, g, u, s.H, s.I, nw, s.T * s.K);
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigGateUpRaw>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, row_token,
+                       row_div, reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wg, wu, g, u, s.H, s.I, nw, s.T * s.K);
+    return hipGetLastError();
+}
+
+// the down pass alone, y = W_down[e] act over expert-sorted rows, with a tile list that launch_big_tile_list wrote
+// (needs H a multiple of 256 and whole k tiles of I)
+bool big_down_applicable(int H, int I) { return H % big::BW == 0 && I % big::BK == 0; }
+hipError_t launch_big_down(const moe_shape_t &s, const bf16_t *act, const void *list, const bf16_t *wd, bf16_t *y_perm,
+                           hipStream_t st) {
+    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int nw2 = s.H / big::BW;
+    hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigPlain>, dim3(8 * tiles_per_xcd * nw2), dim3(256), 0, st, act,
+                       (const int32_t *)nullptr, 1, reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wd, wd, y_perm,
+                       (bf16_t *)nullptr, s.I, s.H, nw2, s.T * s.K);
     return hipGetLastError();
 }
 

@@ -13,7 +13,8 @@ import torch
 from . import moe
 from .moe import MoeShape, _check, _ptr, _stream
 
-EXPORTS = ("moe_backward_workspace_bytes", "moe_grouped_swiglu_backward", "moe_backward", "moe_backward_stage_times")
+EXPORTS = ("moe_backward_workspace_bytes", "moe_grouped_swiglu_backward", "moe_backward", "moe_backward_stage_times",
+           "moe_forward_saving", "moe_backward_saved")
 NUM_STAGES = 13
 STAGE_NAMES = ("route", "permute_copy", "tile_list", "g_gemm", "u_gemm", "dq_gemm", "swiglu_rows", "dx_rows_gemm", "d_w_down",
                "d_w_gate", "d_w_up", "softmax_dx_router", "empty_interval")
@@ -31,6 +32,8 @@ def _lib() -> ctypes.CDLL:
         lib.moe_grouped_swiglu_backward.argtypes = [sp] + [vp] * 11 + [sz, vp]
         lib.moe_backward.argtypes = [sp] + [vp] * 14 + [sz, vp]
         lib.moe_backward_stage_times.argtypes = [sp] + [vp] * 14 + [sz, vp, ctypes.POINTER(ctypes.c_float)]
+        lib.moe_forward_saving.argtypes = [sp] + [vp] * 10 + [sz, vp]
+        lib.moe_backward_saved.argtypes = [sp] + [vp] * 16 + [sz, vp]
         for name in EXPORTS:
             getattr(lib, name).restype = ctypes.c_int
         _ready = True
@@ -73,6 +76,40 @@ def moe_backward(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tenso
     _check(_lib().moe_backward(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
                                _ptr(w_down), _ptr(d_out), _ptr(out["d_x"]), _ptr(out["d_w_router"]), _ptr(out["d_router_bias"]),
                                _ptr(out["d_w_gate"]), _ptr(out["d_w_up"]), _ptr(out["d_w_down"]), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def moe_forward_saving(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tensor], w_gate, w_up, w_down, ws,
+                       out=None, g_rows=None, u_rows=None):
+    """moe_forward that also returns the expert pre-activations of every expert-sorted row: (out, g_rows, u_rows).
+    ws: a forward workspace (moe.alloc_workspace)."""
+    dev, n = x.device, shape.T * shape.K
+    if out is None:
+        out = torch.empty((shape.T, shape.H), dtype=torch.bfloat16, device=dev)
+    if g_rows is None:
+        g_rows = torch.empty((max(n, 1), shape.I), dtype=torch.bfloat16, device=dev)
+    if u_rows is None:
+        u_rows = torch.empty((max(n, 1), shape.I), dtype=torch.bfloat16, device=dev)
+    _check(_lib().moe_forward_saving(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
+                                     _ptr(w_down), _ptr(out), _ptr(g_rows), _ptr(u_rows), _ptr(ws), ws.numel(), _stream()))
+    return out, g_rows, u_rows
+
+
+def moe_backward_saved(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tensor], w_gate, w_up, w_down, d_out, g_rows,
+                       u_rows, ws, out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """moe_backward reading the pre-activations that moe_forward_saving kept.  ws: a backward workspace."""
+    dev = x.device
+    if out is None:
+        out = {"d_x": torch.empty((shape.T, shape.H), dtype=torch.bfloat16, device=dev),
+               "d_w_router": torch.empty((shape.E, shape.H), dtype=torch.float32, device=dev),
+               "d_router_bias": torch.empty((shape.E,), dtype=torch.float32, device=dev),
+               "d_w_gate": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),
+               "d_w_up": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),
+               "d_w_down": torch.empty((shape.E, shape.H, shape.I), dtype=torch.float32, device=dev)}
+    _check(_lib().moe_backward_saved(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
+                                     _ptr(w_down), _ptr(d_out), _ptr(g_rows), _ptr(u_rows), _ptr(out["d_x"]), _ptr(out["d_w_router"]),
+                                     _ptr(out["d_router_bias"]), _ptr(out["d_w_gate"]), _ptr(out["d_w_up"]), _ptr(out["d_w_down"]),
+                                     _ptr(ws), ws.numel(), _stream()))
     return out
 
 

@@ -112,6 +112,13 @@ def test_full_size_backward_on_samples(oracle_lib):
     shp = shape_of(cfg)
     ws = mb.alloc_workspace(shp)
     out = mb.moe_backward(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    # the pair that keeps the pre-activations gives the same bits at this size too
+    _, g_rows, u_rows = mb.moe_forward_saving(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], moe.alloc_workspace(shp))
+    saved = mb.moe_backward_saved(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16),
+                                  g_rows, u_rows, mb.alloc_workspace(shp))
+    for name in out:
+        assert torch.equal(out[name], saved[name]), name
+    del saved, g_rows, u_rows
     o_idx, o_w = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K)
     # d_x of sampled tokens
     tok = np.sort(rng.choice(cfg.T, 24, replace=False))
@@ -127,6 +134,55 @@ def test_full_size_backward_on_samples(oracle_lib):
         _cmp(out["d_w_gate"][e], dwg, f"d_w_gate[{e}]")
         _cmp(out["d_w_up"][e], dwu, f"d_w_up[{e}]")
         _cmp(out["d_w_down"][e], dwd, f"d_w_down[{e}]")
+
+
+SAVING_CASES = [
+    wl.small_config(600, 256, 4, 2, 256, dtype=wl.BF16, seed=61, sigma_w=0.05),       # whole and ragged 256-row tiles
+    wl.small_config(37, 256, 5, 3, 128, dtype=wl.BF16, seed=62, sigma_w=0.05),        # a handful of rows per expert
+    wl.small_config(1100, 512, 16, 4, 384, dtype=wl.BF16, seed=63, sigma_w=0.05),     # with a router bias (odd seed)
+]
+
+
+@pytest.mark.parametrize("cfg", SAVING_CASES, ids=[c.name for c in SAVING_CASES])
+def test_saved_pre_activations_pair(oracle_lib, cfg):
+    """moe_forward_saving + moe_backward_saved: the output against the forward oracle, the gradients against the
+    backward oracle, and bit for bit against moe_backward (whose recomputation yields the same g and u)."""
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    rng = np.random.default_rng(cfg.seed)
+    bias = (rng.standard_normal(cfg.E) * 0.1).astype(np.float32) if cfg.seed % 2 else None
+    bias_dev = None if bias is None else torch.from_numpy(bias).cuda()
+    do_bits, do = _bf16_normal(rng, (cfg.T, cfg.H))
+    shp = shape_of(cfg)
+    out, g_rows, u_rows = mb.moe_forward_saving(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"],
+                                                moe.alloc_workspace(shp))
+    o_out, _, _ = oracle_lib.forward(d["x_f32"], d["w_router_f32"], d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], cfg.K, bias)
+    check_close(host(out), o_out, "out", max_abs=2e-2 * max(1.0, np.abs(o_out).max()))
+    ws = mb.alloc_workspace(shp)
+    got = mb.moe_backward_saved(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16),
+                                g_rows, u_rows, ws)
+    o_idx, o_w = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K, bias)
+    ref = bwd.backward(d["x_f32"], d["w_router_f32"], bias, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx, do, True)
+    for name in ("d_x", "d_w_router", "d_w_gate", "d_w_up", "d_w_down"):
+        _cmp(got[name], ref[name], name)
+    _cmp_bias(got["d_router_bias"], ref, o_idx, o_w)
+    again = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    for name in got:
+        assert torch.equal(got[name], again[name]), name
+
+
+def test_saving_pair_restrictions():
+    shp = moe.make_shape(8, 192, 4, 2, 128, moe.MOE_BF16)           # H not a multiple of 256
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(moe.MoeError) as e:
+        mb.moe_forward_saving(shp, z(8, 192), z(4, 192), None, z(4, 128, 192), z(4, 128, 192), z(4, 192, 128), moe.alloc_workspace(shp))
+    assert e.value.code == 2
+    shp = moe.make_shape(8, 256, 4, 2, 128, moe.MOE_F32)
+    f = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
+    with pytest.raises(moe.MoeError) as e:
+        mb.moe_forward_saving(shp, f(8, 256), f(4, 256), None, f(4, 128, 256), f(4, 128, 256), f(4, 256, 128), moe.alloc_workspace(shp),
+                              out=z(8, 256))
+    assert e.value.code == 3
 
 
 def test_backward_restrictions_and_empty_batch():
