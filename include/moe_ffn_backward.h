@@ -63,8 +63,8 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
                           float *d_w_down, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * moe_forward that also keeps what the backward pass would otherwise recompute (Section 4.1: every rollout token is
- * trained on, so each forward pass of training is followed by its backward pass).
+ * moe_forward that also keeps what the backward pass would otherwise recompute (the trainer of Section 4.1 runs the
+ * policy's forward pass and then its backward pass over the same tokens).
  *   x, w_router, router_bias, w_gate, w_up, w_down, out: as for moe_forward
  *   g_rows, u_rows [T*K, I] bf16 out: g = W_gate[e] x_t and u = W_up[e] x_t of expert-sorted row r (the row order of
  *                                     moe_permute; a pure function of the routing, so moe_backward_saved finds it again)
