@@ -177,12 +177,16 @@ def bench_backward(args):
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
     # the other choice: the forward pass keeps g and u, the backward pass reads them (same gradients, bit for bit)
     fws = moe.alloc_workspace(shp)
-    fout, g_rows, u_rows = mb.moe_forward_saving(shp, x, wr, None, wg, wu, wd, fws)
+    k_idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    k_w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
+    fout, g_rows, u_rows = mb.moe_forward_saving(shp, x, wr, None, wg, wu, wd, fws, topk_idx_out=k_idx, topk_w_out=k_w)
     fwd_plain = moe.moe_forward(shp, x, wr, None, wg, wu, wd, fws)
     pair = {}
     for name, fn in (("forward_ms", lambda: moe.moe_forward(shp, x, wr, None, wg, wu, wd, fws, out=fwd_plain)),
-                     ("forward_saving_ms", lambda: mb.moe_forward_saving(shp, x, wr, None, wg, wu, wd, fws, out=fout, g_rows=g_rows, u_rows=u_rows)),
-                     ("backward_saved_ms", lambda: mb.moe_backward_saved(shp, x, wr, None, wg, wu, wd, d_out, g_rows, u_rows, ws, out=out))):
+                     ("forward_saving_ms", lambda: mb.moe_forward_saving(shp, x, wr, None, wg, wu, wd, fws, out=fout, g_rows=g_rows, u_rows=u_rows,
+                                                                         topk_idx_out=k_idx, topk_w_out=k_w)),
+                     ("backward_saved_ms", lambda: mb.moe_backward_saved(shp, x, wr, None, wg, wu, wd, d_out, g_rows, u_rows, ws, out=out,
+                                                                         topk_idx=k_idx, topk_w=k_w))):
         fn()
         torch.cuda.synchronize()
         c0 = time.perf_counter()

@@ -68,6 +68,7 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
  *   x, w_router, router_bias, w_gate, w_up, w_down, out: as for moe_forward
  *   g_rows, u_rows [T*K, I] bf16 out: g = W_gate[e] x_t and u = W_up[e] x_t of expert-sorted row r (the row order of
  *                                     moe_permute; a pure function of the routing, so moe_backward_saved finds it again)
+ *   topk_idx_out [T,K] int32, topk_w_out [T,K] float out, or NULL: the routing, as from moe_forward
  *   ws: a forward workspace (the size that moe_workspace_bytes gives for `shape`)
  * The activations are formed from the rounded g and u (one rounding more than in moe_forward: same tolerance).
  * Restrictions: MOE_BF16 (else MOE_ERR_DTYPE); H a multiple of 256 and I a multiple of 128 (else MOE_ERR_SHAPE): the
@@ -75,18 +76,21 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
  */
 moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
                                 const void *w_gate, const void *w_up, const void *w_down, void *out, void *g_rows,
-                                void *u_rows, void *ws, size_t ws_bytes, void *stream);
+                                void *u_rows, int32_t *topk_idx_out, float *topk_w_out, void *ws, size_t ws_bytes,
+                                void *stream);
 
 /*
  * moe_backward with the pre-activations supplied instead of recomputed.
  *   g_rows, u_rows [T*K, I] bf16: as written by moe_forward_saving for the same x, router and expert weights
+ *   topk_idx [T,K] int32, topk_w [T,K] float: the routing that moe_forward_saving wrote, or both NULL (then it is recomputed)
  * Everything else as for moe_backward (same workspace size, same results: with g_rows and u_rows from
  * moe_forward_saving the gradients are bit for bit those of moe_backward, whose recomputation yields the same g and u).
  */
 moe_status_t moe_backward_saved(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
                                 const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
-                                const void *g_rows, const void *u_rows, void *d_x, float *d_w_router, float *d_router_bias,
-                                float *d_w_gate, float *d_w_up, float *d_w_down, void *ws, size_t ws_bytes, void *stream);
+                                const void *g_rows, const void *u_rows, const int32_t *topk_idx, const float *topk_w, void *d_x,
+                                float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up, float *d_w_down,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /*
  * moe_backward with a HIP event recorded on `stream` at every stage boundary, for attributing the time of one

@@ -217,14 +217,16 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
 
 moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
                                 const void *w_gate, const void *w_up, const void *w_down, void *out, void *g_rows,
-                                void *u_rows, void *ws, size_t ws_bytes, void *stream) {
+                                void *u_rows, int32_t *topk_idx_out, float *topk_w_out, void *ws, size_t ws_bytes,
+                                void *stream) {
     moe_status_t st = check_shape(shape);
     if (st != MOE_OK) return st;
     if (shape->dtype != MOE_BF16) return MOE_ERR_DTYPE;
     if (!big_pre_activations_applicable(shape->H, shape->I) || !big_down_applicable(shape->H, shape->I)) return MOE_ERR_SHAPE;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !out || !g_rows || !u_rows) return MOE_ERR_NULL;
     if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
-        misaligned(w_down) || misaligned(out) || misaligned(g_rows) || misaligned(u_rows))
+        misaligned(w_down) || misaligned(out) || misaligned(g_rows) || misaligned(u_rows) || misaligned(topk_idx_out) ||
+        misaligned(topk_w_out))
         return MOE_ERR_ALIGN;
     st = check_ws(*shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
@@ -232,9 +234,10 @@ moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const v
     const moe_shape_t &s = *shape;
     Workspace w = carve_workspace(s, ws);
     hipStream_t hs = (hipStream_t)stream;
-    if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs, nullptr) != hipSuccess) return MOE_ERR_HIP;
-    if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs, 0, 0, w.tile_map) !=
-        hipSuccess)
+    int32_t *idx = topk_idx_out ? topk_idx_out : w.topk_idx;
+    float *tw = topk_w_out ? topk_w_out : w.topk_w;
+    if (launch_route(s, x, w_router, router_bias, w.logit_part, idx, tw, hs, nullptr) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_permute(s, idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs, 0, 0, w.tile_map) != hipSuccess)
         return MOE_ERR_HIP;
     if (launch_big_tile_list(s, w.expert_offsets, w.tile_map, hs) != hipSuccess) return MOE_ERR_HIP;
     if (launch_big_pre_activations(s, (const bf16_t *)x, w.row_to_assign, s.K, w.tile_map, (const bf16_t *)w_gate,
@@ -245,7 +248,7 @@ moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const v
                        (const bf16_t *)u_rows, w.act, n8);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
     if (launch_big_down(s, w.act, w.tile_map, (const bf16_t *)w_down, (bf16_t *)w.y_perm, hs) != hipSuccess) return MOE_ERR_HIP;
-    if (launch_combine(s, w.y_perm, w.assign_to_row, w.topk_w, out, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_combine(s, w.y_perm, w.assign_to_row, tw, out, hs) != hipSuccess) return MOE_ERR_HIP;
     return MOE_OK;
 }
 

@@ -383,12 +383,13 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
                                   const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
                                   void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
                                   float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe,
-                                  const void *g_rows = nullptr, const void *u_rows = nullptr) {
+                                  const void *g_rows = nullptr, const void *u_rows = nullptr,
+                                  const int32_t *topk_idx_saved = nullptr, const float *topk_w_saved = nullptr) {
     moe_status_t st = check_bw_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !d_out || !d_x || !d_w_router || !d_w_gate || !d_w_up || !d_w_down)
         return MOE_ERR_NULL;
-    if (misaligned(g_rows) || misaligned(u_rows)) return MOE_ERR_ALIGN;
+    if (misaligned(g_rows) || misaligned(u_rows) || misaligned(topk_idx_saved) || misaligned(topk_w_saved)) return MOE_ERR_ALIGN;
     if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
         misaligned(w_down) || misaligned(d_out) || misaligned(d_x) || misaligned(d_w_router) || misaligned(d_router_bias) ||
         misaligned(d_w_gate) || misaligned(d_w_up) || misaligned(d_w_down))
@@ -410,9 +411,13 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     }
     bf16_t *dxp = (bf16_t *)w.y_perm;
     if (probe) { probe->st = hs; probe->mark(); }
-    if (launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
+    // the routing: the caller's (kept from the forward pass), or recomputed
+    const bool routed = topk_idx_saved && topk_w_saved;
+    const int32_t *topk_idx = routed ? topk_idx_saved : w.topk_idx;
+    const float *topk_w = routed ? topk_w_saved : w.topk_w;
+    if (!routed && launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);
-    if (launch_permute(s, w.topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
+    if (launch_permute(s, topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
     // Shapes the LDS-pipelined GEMMs take: they fetch the rows of x and d_out through a row -> token map (both then stay
     // in the caches instead of being streamed back K times over).  Otherwise: copies of x and d_out in expert-sorted row
@@ -429,13 +434,13 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
         return MOE_ERR_HIP;
     }
     bw_mark(probe);
-    if (expert_backward(s, x_rows, up_rows, row_token, w.row_to_assign, w.topk_w, w.expert_offsets, (const bf16_t *)w_gate,
+    if (expert_backward(s, x_rows, up_rows, row_token, w.row_to_assign, topk_w, w.expert_offsets, (const bf16_t *)w_gate,
                         (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe,
                         (const bf16_t *)g_rows, (const bf16_t *)u_rows) != hipSuccess)
         return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, w.topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
+    hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, w.topk_idx, (const bf16_t *)w_router,
+    hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, topk_idx, (const bf16_t *)w_router,
                        (bf16_t *)d_x, s.H, s.K);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
     hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, x_rows, row_token, b.dw_row, w.expert_offsets,
@@ -456,11 +461,12 @@ moe_status_t moe_backward(const moe_shape_t *shape, const void *x, const void *w
 
 moe_status_t moe_backward_saved(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
                                 const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
-                                const void *g_rows, const void *u_rows, void *d_x, float *d_w_router, float *d_router_bias,
-                                float *d_w_gate, float *d_w_up, float *d_w_down, void *ws, size_t ws_bytes, void *stream) {
-    if (!g_rows || !u_rows) return MOE_ERR_NULL;
+                                const void *g_rows, const void *u_rows, const int32_t *topk_idx, const float *topk_w, void *d_x,
+                                float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up, float *d_w_down,
+                                void *ws, size_t ws_bytes, void *stream) {
+    if (!g_rows || !u_rows || (topk_idx == nullptr) != (topk_w == nullptr)) return MOE_ERR_NULL;
     return backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias, d_w_gate,
-                         d_w_up, d_w_down, ws, ws_bytes, stream, nullptr, g_rows, u_rows);
+                         d_w_up, d_w_down, ws, ws_bytes, stream, nullptr, g_rows, u_rows, topk_idx, topk_w);
 }
 
 moe_status_t moe_backward_stage_times(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,

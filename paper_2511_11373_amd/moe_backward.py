@@ -32,8 +32,8 @@ def _lib() -> ctypes.CDLL:
         lib.moe_grouped_swiglu_backward.argtypes = [sp] + [vp] * 11 + [sz, vp]
         lib.moe_backward.argtypes = [sp] + [vp] * 14 + [sz, vp]
         lib.moe_backward_stage_times.argtypes = [sp] + [vp] * 14 + [sz, vp, ctypes.POINTER(ctypes.c_float)]
-        lib.moe_forward_saving.argtypes = [sp] + [vp] * 10 + [sz, vp]
-        lib.moe_backward_saved.argtypes = [sp] + [vp] * 16 + [sz, vp]
+        lib.moe_forward_saving.argtypes = [sp] + [vp] * 12 + [sz, vp]
+        lib.moe_backward_saved.argtypes = [sp] + [vp] * 18 + [sz, vp]
         for name in EXPORTS:
             getattr(lib, name).restype = ctypes.c_int
         _ready = True
@@ -80,9 +80,9 @@ def moe_backward(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tenso
 
 
 def moe_forward_saving(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tensor], w_gate, w_up, w_down, ws,
-                       out=None, g_rows=None, u_rows=None):
-    """moe_forward that also returns the expert pre-activations of every expert-sorted row: (out, g_rows, u_rows).
-    ws: a forward workspace (moe.alloc_workspace)."""
+                       out=None, g_rows=None, u_rows=None, topk_idx_out=None, topk_w_out=None):
+    """moe_forward that also returns the expert pre-activations of every expert-sorted row: (out, g_rows, u_rows); the
+    routing goes to topk_idx_out / topk_w_out when given.  ws: a forward workspace (moe.alloc_workspace)."""
     dev, n = x.device, shape.T * shape.K
     if out is None:
         out = torch.empty((shape.T, shape.H), dtype=torch.bfloat16, device=dev)
@@ -91,13 +91,15 @@ def moe_forward_saving(shape: MoeShape, x, w_router, router_bias: Optional[torch
     if u_rows is None:
         u_rows = torch.empty((max(n, 1), shape.I), dtype=torch.bfloat16, device=dev)
     _check(_lib().moe_forward_saving(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
-                                     _ptr(w_down), _ptr(out), _ptr(g_rows), _ptr(u_rows), _ptr(ws), ws.numel(), _stream()))
+                                     _ptr(w_down), _ptr(out), _ptr(g_rows), _ptr(u_rows), _ptr(topk_idx_out), _ptr(topk_w_out), _ptr(ws),
+                                     ws.numel(), _stream()))
     return out, g_rows, u_rows
 
 
 def moe_backward_saved(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tensor], w_gate, w_up, w_down, d_out, g_rows,
-                       u_rows, ws, out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
-    """moe_backward reading the pre-activations that moe_forward_saving kept.  ws: a backward workspace."""
+                       u_rows, ws, out: Optional[Dict[str, torch.Tensor]] = None, topk_idx=None, topk_w=None) -> Dict[str, torch.Tensor]:
+    """moe_backward reading the pre-activations (and, when given, the routing) that moe_forward_saving kept.
+    ws: a backward workspace."""
     dev = x.device
     if out is None:
         out = {"d_x": torch.empty((shape.T, shape.H), dtype=torch.bfloat16, device=dev),
@@ -107,7 +109,8 @@ def moe_backward_saved(shape: MoeShape, x, w_router, router_bias: Optional[torch
                "d_w_up": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),
                "d_w_down": torch.empty((shape.E, shape.H, shape.I), dtype=torch.float32, device=dev)}
     _check(_lib().moe_backward_saved(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
-                                     _ptr(w_down), _ptr(d_out), _ptr(g_rows), _ptr(u_rows), _ptr(out["d_x"]), _ptr(out["d_w_router"]),
+                                     _ptr(w_down), _ptr(d_out), _ptr(g_rows), _ptr(u_rows), _ptr(topk_idx), _ptr(topk_w), _ptr(out["d_x"]),
+                                     _ptr(out["d_w_router"]),
                                      _ptr(out["d_router_bias"]), _ptr(out["d_w_gate"]), _ptr(out["d_w_up"]), _ptr(out["d_w_down"]),
                                      _ptr(ws), ws.numel(), _stream()))
     return out

@@ -154,8 +154,10 @@ def test_saved_pre_activations_pair(oracle_lib, cfg):
     bias_dev = None if bias is None else torch.from_numpy(bias).cuda()
     do_bits, do = _bf16_normal(rng, (cfg.T, cfg.H))
     shp = shape_of(cfg)
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    wgt = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
     out, g_rows, u_rows = mb.moe_forward_saving(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"],
-                                                moe.alloc_workspace(shp))
+                                                moe.alloc_workspace(shp), topk_idx_out=idx, topk_w_out=wgt)
     o_out, _, _ = oracle_lib.forward(d["x_f32"], d["w_router_f32"], d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], cfg.K, bias)
     check_close(host(out), o_out, "out", max_abs=2e-2 * max(1.0, np.abs(o_out).max()))
     ws = mb.alloc_workspace(shp)
@@ -166,9 +168,15 @@ def test_saved_pre_activations_pair(oracle_lib, cfg):
     for name in ("d_x", "d_w_router", "d_w_gate", "d_w_up", "d_w_down"):
         _cmp(got[name], ref[name], name)
     _cmp_bias(got["d_router_bias"], ref, o_idx, o_w)
+    assert np.array_equal(host(idx), o_idx)
     again = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
     for name in got:
         assert torch.equal(got[name], again[name]), name
+    # ... and with the routing kept too
+    kept = mb.moe_backward_saved(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16),
+                                 g_rows, u_rows, ws, topk_idx=idx, topk_w=wgt)
+    for name in got:
+        assert torch.equal(got[name], kept[name]), name
 
 
 def test_saving_pair_restrictions():
