@@ -171,16 +171,26 @@ moe_status_t moe_combine(const moe_shape_t *shape, const void *y_perm, const int
                ? MOE_OK : MOE_ERR_HIP;
 }
 
-static moe_status_t forward_impl(const moe_shape_t *shape, const void *x, const void *w_router,
-                                 const float *router_bias, const void *w_gate, const void *w_up,
-                                 const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
-                                 void *ws, size_t ws_bytes, void *stream, Probe *probe) {
+// Host-side checks of moe_forward's arguments other than the workspace (no HIP call).
+static moe_status_t check_forward_args(const moe_shape_t *shape, const void *x, const void *w_router,
+                                       const float *router_bias, const void *w_gate, const void *w_up,
+                                       const void *w_down, const void *out, const int32_t *topk_idx_out,
+                                       const float *topk_w_out) {
     moe_status_t st = check_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !out) return MOE_ERR_NULL;
     if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
         misaligned(w_down) || misaligned(out) || misaligned(topk_idx_out) || misaligned(topk_w_out))
         return MOE_ERR_ALIGN;
+    return MOE_OK;
+}
+
+static moe_status_t forward_impl(const moe_shape_t *shape, const void *x, const void *w_router,
+                                 const float *router_bias, const void *w_gate, const void *w_up,
+                                 const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                                 void *ws, size_t ws_bytes, void *stream, Probe *probe) {
+    moe_status_t st = check_forward_args(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out);
+    if (st != MOE_OK) return st;
     st = check_ws(*shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
     if (shape->T == 0) return MOE_OK;
@@ -258,11 +268,20 @@ moe_status_t moe_forward_stage_times(const moe_shape_t *shape, const void *x, co
                                      float *stage_ms) {
     if (!stage_ms) return MOE_ERR_NULL;
     for (int i = 0; i < MOE_NUM_STAGES; ++i) stage_ms[i] = 0.f;
-    if (shape && shape->T == 0) return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr, ws, ws_bytes, stream, nullptr);
+    // the arguments are checked before the first HIP call, here as everywhere; the events are the one thing any
+    // entry point of the library creates, and they are destroyed before it returns
+    moe_status_t st = check_forward_args(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr);
+    if (st != MOE_OK) return st;
+    st = check_ws(*shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
     Probe probe;
     for (int i = 0; i <= MOE_NUM_STAGES; ++i)
-        if (hipEventCreate(&probe.ev[i]) != hipSuccess) return MOE_ERR_HIP;
-    moe_status_t st = forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr, ws,
+        if (hipEventCreate(&probe.ev[i]) != hipSuccess) {
+            while (--i >= 0) (void)hipEventDestroy(probe.ev[i]);
+            return MOE_ERR_HIP;
+        }
+    st = forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, nullptr, nullptr, ws,
                                    ws_bytes, stream, &probe);
     if (st == MOE_OK && probe.n == MOE_NUM_STAGES + 1) {
         if (hipEventSynchronize(probe.ev[MOE_NUM_STAGES]) != hipSuccess) st = MOE_ERR_HIP;

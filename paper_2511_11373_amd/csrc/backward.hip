@@ -8,7 +8,8 @@
 //   y = Wd a, a = silu(g) u          da = w_k (d_out_t Wd),  dWd_e += d_out_t (x) (w_k a)
 //   g = Wg x, u = Wu x               dg = da u silu'(g),  du = da silu(g),  silu'(g) = s (1 + g (1 - s)),  s = 1/(1+e^-g)
 //                                    dWg_e += dg (x) x_t,  dWu_e += du (x) x_t,  dx_t += dg Wg + du Wu
-// g, u are recomputed from x (nothing is kept from a forward call).  Intermediates are bf16, sums are float.
+// moe_backward recomputes g, u from x (it takes nothing from a forward call); moe_backward_saved reads the g, u that
+// moe_forward_saving wrote.  Intermediates are bf16, sums are float.
 #include <type_traits>
 
 #include "moe_internal.hpp"
@@ -379,17 +380,16 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
                            d_w_gate, d_w_up, d_w_down, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
-                                  const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
-                                  void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
-                                  float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe,
-                                  const void *g_rows = nullptr, const void *u_rows = nullptr,
-                                  const int32_t *topk_idx_saved = nullptr, const float *topk_w_saved = nullptr) {
+// Host-side checks of moe_backward's arguments (no HIP call).
+static moe_status_t check_backward_args(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                        const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                        const void *d_x, const float *d_w_router, const float *d_router_bias,
+                                        const float *d_w_gate, const float *d_w_up, const float *d_w_down, const void *ws,
+                                        size_t ws_bytes) {
     moe_status_t st = check_bw_shape(shape);
     if (st != MOE_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !d_out || !d_x || !d_w_router || !d_w_gate || !d_w_up || !d_w_down)
         return MOE_ERR_NULL;
-    if (misaligned(g_rows) || misaligned(u_rows) || misaligned(topk_idx_saved) || misaligned(topk_w_saved)) return MOE_ERR_ALIGN;
     if (misaligned(x) || misaligned(w_router) || misaligned(router_bias) || misaligned(w_gate) || misaligned(w_up) ||
         misaligned(w_down) || misaligned(d_out) || misaligned(d_x) || misaligned(d_w_router) || misaligned(d_router_bias) ||
         misaligned(d_w_gate) || misaligned(d_w_up) || misaligned(d_w_down))
@@ -397,6 +397,19 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     if (!ws) return MOE_ERR_WORKSPACE;
     if (misaligned(ws)) return MOE_ERR_ALIGN;
     if (ws_bytes < carve_bw(*shape, nullptr).total) return MOE_ERR_WORKSPACE;
+    return MOE_OK;
+}
+
+static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,
+                                  const void *w_gate, const void *w_up, const void *w_down, const void *d_out,
+                                  void *d_x, float *d_w_router, float *d_router_bias, float *d_w_gate, float *d_w_up,
+                                  float *d_w_down, void *ws, size_t ws_bytes, void *stream, BwProbe *probe,
+                                  const void *g_rows = nullptr, const void *u_rows = nullptr,
+                                  const int32_t *topk_idx_saved = nullptr, const float *topk_w_saved = nullptr) {
+    moe_status_t st = check_backward_args(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router,
+                                          d_router_bias, d_w_gate, d_w_up, d_w_down, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    if (misaligned(g_rows) || misaligned(u_rows) || misaligned(topk_idx_saved) || misaligned(topk_w_saved)) return MOE_ERR_ALIGN;
     hipStream_t hs = (hipStream_t)stream;
     const moe_shape_t &s = *shape;
     BwWorkspace b = carve_bw(s, ws);
@@ -475,11 +488,18 @@ moe_status_t moe_backward_stage_times(const moe_shape_t *shape, const void *x, c
                                       float *d_w_down, void *ws, size_t ws_bytes, void *stream, float *stage_ms) {
     if (!stage_ms) return MOE_ERR_NULL;
     for (int i = 0; i < MOE_BW_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+    // arguments are checked before the first HIP call; the events are destroyed before the call returns
+    moe_status_t st = check_backward_args(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router,
+                                          d_router_bias, d_w_gate, d_w_up, d_w_down, ws, ws_bytes);
+    if (st != MOE_OK) return st;
     BwProbe probe;
-    const bool timed = shape && shape->T > 0;
+    const bool timed = shape->T > 0;
     for (int i = 0; timed && i <= MOE_BW_NUM_STAGES; ++i)
-        if (hipEventCreate(&probe.ev[i]) != hipSuccess) return MOE_ERR_HIP;
-    moe_status_t st = backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias,
+        if (hipEventCreate(&probe.ev[i]) != hipSuccess) {
+            while (--i >= 0) (void)hipEventDestroy(probe.ev[i]);
+            return MOE_ERR_HIP;
+        }
+    st = backward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, d_out, d_x, d_w_router, d_router_bias,
                                     d_w_gate, d_w_up, d_w_down, ws, ws_bytes, stream, timed ? &probe : nullptr);
     if (timed && st == MOE_OK && probe.n == MOE_BW_NUM_STAGES + 1) {
         if (hipEventSynchronize(probe.ev[MOE_BW_NUM_STAGES]) != hipSuccess) st = MOE_ERR_HIP;
