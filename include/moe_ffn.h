@@ -62,7 +62,8 @@ typedef enum {
     MOE_ERR_DTYPE = 3,      /* dtype is neither MOE_BF16 nor MOE_F32 */
     MOE_ERR_WORKSPACE = 4,  /* ws is NULL or ws_bytes is below moe_workspace_bytes() */
     MOE_ERR_ALIGN = 5,      /* a data pointer is not 16-byte aligned */
-    MOE_ERR_HIP = 6         /* a kernel launch reported an error */
+    MOE_ERR_HIP = 6,        /* a kernel launch (or another HIP call) reported an error */
+    MOE_ERR_STATIC_LIMIT = 7 /* moe_forward_noalloc: the shape needs more than MOE_NOALLOC_SCRATCH_BYTES of scratch */
 } moe_status_t;
 
 typedef enum { MOE_BF16 = 0, MOE_F32 = 1 } moe_dtype_t;
@@ -146,6 +147,25 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
                          const float *router_bias, const void *w_gate, const void *w_up,
                          const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
                          void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * moe_forward for callers that cannot allocate device memory or hand over a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus ws / ws_bytes),
+ * kernels, results and errors as moe_forward; the scratch is a buffer of MOE_NOALLOC_SCRATCH_BYTES that is part of
+ * the loaded library (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ *   - A shape whose moe_workspace_bytes() exceeds MOE_NOALLOC_SCRATCH_BYTES is rejected with
+ *     MOE_ERR_STATIC_LIMIT before anything is enqueued (32 MiB covers decode batches of up to 512 tokens at
+ *     H 2048, E 128, K 8, I 768).
+ *   - The first call on a GPU looks up that GPU's copy of the buffer (hipGetSymbolAddress); a failure there is
+ *     MOE_ERR_HIP.
+ *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents: calls that overlap
+ *     in time on one GPU (different streams, different threads) race.  Calls on one stream are ordered and safe.
+ */
+#define MOE_NOALLOC_SCRATCH_BYTES (32u << 20)
+moe_status_t moe_forward_noalloc(const moe_shape_t *shape, const void *x, const void *w_router,
+                                 const float *router_bias, const void *w_gate, const void *w_up,
+                                 const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                                 void *stream);
 
 /*
  * moe_forward with a HIP event recorded on `stream` at every stage boundary, for

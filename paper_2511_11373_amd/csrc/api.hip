@@ -2,8 +2,36 @@
 // call), workspace carving, and the launch sequences.
 #include "moe_internal.hpp"
 #include <algorithm>
+#include <mutex>
 
 namespace moe {
+
+// Scratch of moe_forward_noalloc: device memory that belongs to the loaded library itself, one copy per GPU, so that
+// the call needs neither a workspace from the caller nor an allocation.  In host code the array's name is only a
+// stand-in for the symbol; the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[MOE_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void *scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, nullptr until asked for
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+static hipError_t static_scratch(void **out) {
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
 
 static moe_status_t check_shape(const moe_shape_t *s) {
     if (!s) return MOE_ERR_NULL;
@@ -94,6 +122,7 @@ const char *moe_status_string(moe_status_t status) {
         case MOE_ERR_WORKSPACE: return "workspace missing or too small";
         case MOE_ERR_ALIGN: return "pointer not 16-byte aligned";
         case MOE_ERR_HIP: return "HIP launch error";
+        case MOE_ERR_STATIC_LIMIT: return "shape needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -223,6 +252,22 @@ moe_status_t moe_forward(const moe_shape_t *shape, const void *x, const void *w_
                          void *ws, size_t ws_bytes, void *stream) {
     return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out, ws,
                         ws_bytes, stream, nullptr);
+}
+
+moe_status_t moe_forward_noalloc(const moe_shape_t *shape, const void *x, const void *w_router,
+                                 const float *router_bias, const void *w_gate, const void *w_up,
+                                 const void *w_down, void *out, int32_t *topk_idx_out, float *topk_w_out,
+                                 void *stream) {
+    // everything that can be rejected on the host is rejected before the first HIP call
+    moe_status_t st = check_forward_args(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out);
+    if (st != MOE_OK) return st;
+    if (carve_workspace(*shape, nullptr).total > (size_t)MOE_NOALLOC_SCRATCH_BYTES) return MOE_ERR_STATIC_LIMIT;
+    if (shape->T == 0) return MOE_OK;
+    void *ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return MOE_ERR_HIP;
+    // No region of the workspace has to start at zero: every kernel of the forward pass writes what it later reads.
+    return forward_impl(shape, x, w_router, router_bias, w_gate, w_up, w_down, out, topk_idx_out, topk_w_out, ws,
+                        (size_t)MOE_NOALLOC_SCRATCH_BYTES, stream, nullptr);
 }
 
 moe_status_t moe_forward_saving(const moe_shape_t *shape, const void *x, const void *w_router, const float *router_bias,

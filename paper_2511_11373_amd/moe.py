@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libmoe_ffn.so")
 
 MOE_BF16, MOE_F32 = 0, 1
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_topk", "moe_permute",
-           "moe_grouped_swiglu", "moe_combine", "moe_forward", "moe_forward_stage_times")
+           "moe_grouped_swiglu", "moe_combine", "moe_forward", "moe_forward_noalloc", "moe_forward_stage_times")
+NOALLOC_SCRATCH_BYTES = 32 << 20
 NUM_STAGES = 8
 STAGE_NAMES = ("router_logits", "topk", "permute", "tile_list", "gate_up_gemm", "down_gemm", "combine", "empty_interval")
 
@@ -54,6 +55,7 @@ def load_library() -> ctypes.CDLL:
         lib.moe_grouped_swiglu.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp]
         lib.moe_forward.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_forward_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.moe_forward_stage_times.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                                 ctypes.POINTER(ctypes.c_float)]
         for name in EXPORTS[1:]:
@@ -141,6 +143,16 @@ def moe_forward(shape: MoeShape, x, w_router, router_bias, w_gate, w_up, w_down,
     _check(load_library().moe_forward(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate),
                                       _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(topk_idx_out), _ptr(topk_w_out),
                                       _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def moe_forward_noalloc(shape: MoeShape, x, w_router, router_bias, w_gate, w_up, w_down, out,
+                        topk_idx_out=None, topk_w_out=None) -> torch.Tensor:
+    """moe_forward on the library's own static scratch: no workspace argument; the call itself allocates nothing, so
+    `out` is the caller's."""
+    _check(load_library().moe_forward_noalloc(ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias),
+                                              _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(topk_idx_out),
+                                              _ptr(topk_w_out), _stream()))
     return out
 
 
