@@ -64,6 +64,8 @@ def parse():
     ap.add_argument("--workload", default="decode64",
                     choices=["tiny", "decode64", "decode512", "prefill16k", "skew4k", "logprob16k", "backward16k", "sched", "attn64"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--no-prefill-record", action="store_true",
+                    help="decode64 only: skip the prefill16k sub-record (layer.prefill16k) measured in the same run")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -396,66 +398,107 @@ def main():
     sets = [(dev(d["w_gate"]), dev(d["w_up"]), dev(d["w_down"]))]
     for s in range(1, WEIGHT_SETS):     # equally distributed sets at other addresses: experts rotated by s
         sets.append(tuple(torch.roll(w, shifts=s, dims=0).contiguous() for w in sets[0]))
-    shp = moe.make_shape(cfg.T, cfg.H, cfg.E, cfg.K, cfg.I, moe.MOE_BF16 if bf16 else moe.MOE_F32, cfg.renormalize)
-    ws = moe.alloc_workspace(shp)
-    out = torch.empty((cfg.T, cfg.H), dtype=x.dtype, device="cuda")
-    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
 
-    def step(i, idx_out=None):
-        wg, wu, wd = sets[i % WEIGHT_SETS]
-        moe.moe_forward(shp, x, wr, bias, wg, wu, wd, ws, out=out, topk_idx_out=idx_out)
+    def measure(cfg, x, bias, steps, warmup):
+        """Times `steps` forward passes of `cfg` over the rotating weight sets; then the per-stage event times and the
+        realised routing of the same step.  Returns (ms_per_step, stage means [ms], load histogram, out, step)."""
+        shp = moe.make_shape(cfg.T, cfg.H, cfg.E, cfg.K, cfg.I, moe.MOE_BF16 if bf16 else moe.MOE_F32, cfg.renormalize)
+        ws = moe.alloc_workspace(shp)
+        out = torch.empty((cfg.T, cfg.H), dtype=x.dtype, device="cuda")
+        idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
 
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / steps
+        def step(i, idx_out=None):
+            wg, wu, wd = sets[i % WEIGHT_SETS]
+            moe.moe_forward(shp, x, wr, bias, wg, wu, wd, ws, out=out, topk_idx_out=idx_out)
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        # realised routing (after the timed region): active experts and load histogram
+        step(0, idx_out=idx)
+        torch.cuda.synchronize()
+        load = np.bincount(idx.cpu().numpy().ravel(), minlength=cfg.E)
+        # per-stage HIP-event times of the same step (the library records an event at every stage boundary)
+        stage = np.zeros(moe.NUM_STAGES)
+        n_prof = max(10, min(steps, 100))
+        for i in range(n_prof):
+            wg, wu, wd = sets[i % WEIGHT_SETS]
+            _, sms = moe.moe_forward_stage_times(shp, x, wr, bias, wg, wu, wd, ws, out=out)
+            stage += np.array(sms)
+        return ms, stage / n_prof, load, out, step
+
+    ms_per_step, stage, load, out, step = measure(cfg, x, bias, steps, warmup)
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
-
-    # realised routing (after the timed region): active experts and load histogram
-    step(0, idx_out=idx)
-    torch.cuda.synchronize()
-    load = np.bincount(idx.cpu().numpy().ravel(), minlength=cfg.E)
     e_act = int((load > 0).sum())
-
-    # per-stage HIP-event times of the same step (the library records an event at every stage boundary)
-    stage = np.zeros(moe.NUM_STAGES)
-    n_prof = max(10, min(steps, 100))
-    for i in range(n_prof):
-        wg, wu, wd = sets[i % WEIGHT_SETS]
-        _, ms = moe.moe_forward_stage_times(shp, x, wr, bias, wg, wu, wd, ws, out=out)
-        stage += np.array(ms)
-    stage /= n_prof
     stages_ms = {n: round(float(v), 5) for n, v in zip(moe.STAGE_NAMES, stage)}
 
     # roofline of the dominant kernel, the gate/up GEMM (2/3 of the weight bytes and of the flops)
     # a stage interval = the kernel plus what recording two events around it costs; the library also times an
     # empty interval, which is subtracted
-    gu_ms = float(stage[moe.STAGE_NAMES.index("gate_up_gemm")] - stage[moe.STAGE_NAMES.index("empty_interval")])
+    empty_ms = float(stage[moe.STAGE_NAMES.index("empty_interval")])
+    gu_ms = float(stage[moe.STAGE_NAMES.index("gate_up_gemm")]) - empty_ms
     gu_bytes = e_act * 2 * cfg.I * cfg.H * elt + cfg.T * cfg.H * elt + cfg.T * cfg.K * cfg.I * 2
     gu_flops = 2.0 * cfg.T * cfg.K * 2 * cfg.I * cfg.H
     layer_bytes = e_act * 3 * cfg.I * cfg.H * elt + cfg.E * cfg.H * elt + 2 * cfg.T * cfg.H * elt
     layer_flops = 2.0 * cfg.T * cfg.K * 3 * cfg.I * cfg.H
+    hbm_whole = layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+    mfma_whole = layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+    traffic = measured_traffic(cfg.name)
+    # `traffic` is not read in this run: it is the figure recorded from two rocprofv3 --pmc runs of this script, kept
+    # with a hash of the kernel source it was taken for, and null once that source has changed
+    traffic_note = None if traffic is None else (
+        "recorded rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/hbm_traffic.md), valid for "
+        f"{TRAFFIC[cfg.name]['source']} sha256 {TRAFFIC[cfg.name]['sha256_16']}; not re-read in this run")
     if cfg.name in HBM_BOUND or cfg.name == "tiny":
         ach = gu_bytes / (gu_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gate_up_gemm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name),
+        roofline = {"bound": "hbm", "kernel": "gate_up_gemm", "scope": "dominant kernel only; whole step: whole_step_frac",
+                    "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "whole_step_frac": round(hbm_whole, 4),
+                    "traffic": traffic, "traffic_source": traffic_note,
                     "bytes_per_launch": int(gu_bytes), "avg_launch_ms": round(gu_ms, 5)}
     else:
         ach = gu_flops / (gu_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gate_up_gemm", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": measured_traffic(cfg.name),
+        roofline = {"bound": "mfma", "kernel": "gate_up_gemm", "scope": "dominant kernel only; whole step: whole_step_frac",
+                    "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "whole_step_frac": round(mfma_whole, 4),
+                    "traffic": traffic, "traffic_source": traffic_note,
                     "flops_per_launch": gu_flops, "avg_launch_ms": round(gu_ms, 5)}
     layer = {"active_experts": e_act, "load_max": int(load.max()), "load_median": float(np.median(load)),
              "load_empty": int((load == 0).sum()),
              "algorithmic_GB": round(layer_bytes / 1e9, 4), "algorithmic_GFLOP": round(layer_flops / 1e9, 2),
-             "hbm_frac_whole_step": round(layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-             "mfma_frac_whole_step": round(layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "hbm_frac_whole_step": round(hbm_whole, 4),
+             "mfma_frac_whole_step": round(mfma_whole, 4),
              "stages_ms": stages_ms}
+
+    # The metric has a prefill half (% of the bf16 matrix-core peak at 16384 tokens).  The default run measures it too,
+    # in the same process, on the same weight sets and rotation: the layer shape is the same, only the batch differs.
+    if cfg.name == "decode64" and not args.no_prefill_record:
+        pcfg = wl.CONFIGS["prefill16k"]
+        px = dev(wl.make_inputs(pcfg, want_f32=False, only=("x",))["x"])
+        p_steps = 20
+        p_ms, p_stage, p_load, p_out, _ = measure(pcfg, px, None, p_steps, 4)
+        p_flops = 2.0 * pcfg.T * pcfg.K * 3 * pcfg.I * pcfg.H
+        p_empty = float(p_stage[moe.STAGE_NAMES.index("empty_interval")])
+        p_gu = float(p_stage[moe.STAGE_NAMES.index("gate_up_gemm")]) - p_empty
+        p_dn = float(p_stage[moe.STAGE_NAMES.index("down_gemm")]) - p_empty
+        layer["prefill16k"] = {
+            "workload": "prefill16k", "tokens": pcfg.T, "steps": p_steps, "warmup": 4, "ms_per_step": round(p_ms, 5),
+            "tokens_per_s": round(pcfg.T / (p_ms * 1e-3), 1), "algorithmic_GFLOP": round(p_flops / 1e9, 2),
+            "mfma_frac_whole_step": round(p_flops / (p_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "gate_up_gemm": {"avg_launch_ms": round(p_gu, 5),
+                             "mfma_frac": round(p_flops * (2.0 / 3.0) / (p_gu * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "down_gemm": {"avg_launch_ms": round(p_dn, 5),
+                          "mfma_frac": round(p_flops / 3.0 / (p_dn * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "stages_ms": {n: round(float(v), 5) for n, v in zip(moe.STAGE_NAMES, p_stage)},
+            "load_max": int(p_load.max()), "load_median": float(np.median(p_load)),
+            "finite": bool(torch.isfinite(p_out.float()).all().item()),
+        }
+        del px, p_out
 
     cpu = None
     if want_cpu:

@@ -241,10 +241,7 @@ hipError_t launch_grouped_swiglu_stream(const moe_shape_t &s, const bf16_t *x_ro
                                         bf16_t *act, bf16_t *y_perm, hipStream_t st, Probe *probe);
 
 constexpr int kWW = 2, kWT = 2, kMW = 1, kMT = 1;      // wave grid and MFMA tiles per wave of the tiled kernel
-#ifndef MOE_SMALL_BK
-#define MOE_SMALL_BK 64
-#endif
-constexpr int kBK = MOE_SMALL_BK;
+constexpr int kBK = 64;                                 // k tile of the tiled kernel
 int gemm_tile_rows(const moe_shape_t &s) {
     if (stream_gemm_applicable(s) || big_gemm_applicable(s)) return 0;      // no tile list, or one of their own
     return kWT * kMT * 32;

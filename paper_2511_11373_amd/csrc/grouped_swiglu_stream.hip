@@ -14,14 +14,8 @@
 namespace moe {
 
 namespace stream {
-#ifndef MOE_NIG
-#define MOE_NIG 2
-#endif
-#ifndef MOE_NID
-#define MOE_NID 1
-#endif
-constexpr int NIG = MOE_NIG;           // items per block, gate/up
-constexpr int NID = MOE_NID;           // items per wave, down
+constexpr int NIG = 2;                // items per block, gate/up (measured best among 1, 2, 4)
+constexpr int NID = 1;                // items per wave, down (measured best among 1, 2)
 constexpr int GROW = 1024 + 16;       // LDS bytes per staged gate/up row piece (1 KB + pad: conflict-free reads)
 constexpr int DHALF = 768 + 16;       // LDS bytes per staged half row of Wd (I = 768 only)
 }  // namespace stream

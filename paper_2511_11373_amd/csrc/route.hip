@@ -2,10 +2,15 @@
 // weights with one wavefront per token.
 //
 // The logit of (token, expert) is the dot product of two rows of bf16 (or float)
-// numbers.  Every such product is exact in double, and for inputs of ordinary
-// dynamic range so is their sum, so the float the sum is rounded to does not
-// depend on the order of summation.  That is what lets an independently written
-// reference reproduce the selection bit for bit.
+// numbers.  Every bf16 x bf16 product is exact in double (16 significant bits),
+// and for bf16 inputs whose magnitudes span less than about 2^18 a sum of 2048
+// of them still fits the 53 bits, so the float the sum is rounded to does not
+// depend on the order of summation; that is what lets an independently written
+// reference reproduce the selection bit for bit.  Outside that range (float
+// storage, whose products have up to 48 bits, or bf16 values of very different
+// magnitudes in one row) the additions round at 2^-53 relative and two orders
+// of summation can, rarely, land on different sides of a float rounding
+// boundary: the result is then one of the two neighbouring floats.
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -249,13 +254,19 @@ __global__ __launch_bounds__(256) void topk_rank_kernel(const double *__restrict
 // router rows that a rigorous error radius needs; kernel 2 recomputes in double only the candidates that could be
 // among the K largest, and ranks those.
 //
-// Error radius.  |fast - exact| <= kGamma * |x_t|_2 * |w_e|_2 + 4e-7 * (1 + |fast|): the fast logit is a sum of
-// H <= 2048 products (each exact in float) accumulated by up to 64 chained 32-term MFMAs, plus the bias add.
-// Allowing each MFMA an error of 2^-21 of the magnitude it handles gives 2^-15 * sum|x_h w_h| in all;
-// Cauchy-Schwarz bounds that sum by the norms; kGamma = 2^-14 doubles it.
+// Error radius.  |fast - exact| <= kGamma * |x_t|_2 * |w_e|_2 + 4e-7 * (1 + |fast|).  The fast logit is a chain of
+// H/32 <= 64 matrix-core instructions, each adding 32 products (exact in float: 16 significant bits) to the running
+// float sum.  How the hardware adds those 33 numbers is not documented; the bound assumes no more than that each of
+// them is kept to 24 bits below the largest of the instruction (aligned to the largest exponent and cut), i.e. an
+// error of at most 33 * 2^-23 * (sum of the magnitudes seen so far) per instruction, final rounding included.  Over
+// 64 instructions that is 64 * 33 * 2^-23 = 2^-11.96 times sum_h |x_h w_h|, which Cauchy-Schwarz bounds by the
+// product of the norms; kGamma = 2^-11.5 leaves a third on top.  The second term covers the bias add and the float
+// arithmetic of the radius itself.  Random rounding errors stay orders of magnitude below this (a float emulation of
+// the chain on rows built for heavy cancellation: 1e-8 of the norms' product), so the price is a few per cent more
+// candidates, not correctness resting on a guess.
 // Candidates.  With lo_e = fast_e - r_e and hi_e = fast_e + r_e, the K-th largest lo is a lower bound tau of the
 // K-th largest exact logit, so every member of the exact top K (ties included) has hi_e >= tau.
-constexpr float kGamma = 6.103515625e-05f;
+constexpr float kGamma = 3.4526698300124393e-04f;      // 2^-11.5
 
 // Butterfly partners inside a row of 16 lanes through the data-parallel-primitive lane permutations: lanes l^1 and
 // l^2 (quad permutations), then the mirror images inside 8 and 16 lanes, which pair every group of 4 (8) lanes

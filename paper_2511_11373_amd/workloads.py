@@ -146,7 +146,7 @@ def zipf_router_bias(cfg: MoEConfig) -> np.ndarray:
     return bias
 
 
-def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True) -> Dict[str, np.ndarray]:
+def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True, only=None) -> Dict[str, np.ndarray]:
     """Draw x, the router weight, the three expert weights and the router bias.
 
     Returns a dict with, for every tensor name in (x, w_router, w_gate, w_up,
@@ -155,17 +155,21 @@ def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True) -> D
     left out when `want_f32` is false).
     `router_bias` is float32 [E] or None.  `weight_set` > 0 draws a different,
     equally distributed set of expert weights (for cache-defeating rotation in
-    benchmarks); x and the router are unchanged.
+    benchmarks); x and the router are unchanged.  `only` restricts the tensors
+    drawn to the names listed (each tensor has its own stream, so the values are
+    the same as in a full draw).
     """
     T, H, E, I = cfg.T, cfg.H, cfg.E, cfg.I
     base = 16 * weight_set
-    raw = {
-        "x": _normal(cfg.seed, 1, (T, H), 1.0),
-        "w_router": _normal(cfg.seed, 2, (E, H), cfg.sigma_w),
-        "w_gate": _normal(cfg.seed, 3 + base, (E, I, H), cfg.sigma_w),
-        "w_up": _normal(cfg.seed, 4 + base, (E, I, H), cfg.sigma_w),
-        "w_down": _normal(cfg.seed, 5 + base, (E, H, I), cfg.sigma_w),
+    recipe = {
+        "x": (1, (T, H), 1.0),
+        "w_router": (2, (E, H), cfg.sigma_w),
+        "w_gate": (3 + base, (E, I, H), cfg.sigma_w),
+        "w_up": (4 + base, (E, I, H), cfg.sigma_w),
+        "w_down": (5 + base, (E, H, I), cfg.sigma_w),
     }
+    raw = {k: _normal(cfg.seed, stream, shape, sigma) for k, (stream, shape, sigma) in recipe.items()
+           if only is None or k in only}
     out: Dict[str, np.ndarray] = {}
     for k, v in raw.items():
         if cfg.dtype == BF16:
@@ -184,6 +188,38 @@ def make_inputs(cfg: MoEConfig, weight_set: int = 0, want_f32: bool = True) -> D
 def small_config(T: int, H: int, E: int, K: int, I: int, dtype: str = F32, seed: int = 0,
                  renormalize: bool = True, sigma_w: float = 0.02) -> MoEConfig:
     return MoEConfig(f"T{T}H{H}E{E}K{K}I{I}", T, H, E, K, I, dtype, renormalize, None, seed, sigma_w)
+
+
+def make_cancelling_router_inputs(T: int, H: int, E: int, seed: int, amp: float = 4.0, sigma_w: float = 0.02):
+    """Token rows and router rows (bf16 bits) built so that unrelated router rows of LARGE norm get equal or nearly
+    equal exact logits for every token, through heavy cancellation.
+
+    Column j + H/4 of x repeats column j for j < H/4.  On those columns every router row carries +a at j and -a at
+    j + H/4 with its own independent a ~ N(0, amp^2): the pairs contribute exactly zero to every exact logit, whatever
+    the token, but the partners lie a quarter of the row apart, so an implementation that accumulates in a narrower type
+    carries a partial sum of size amp * sqrt(H) through hundreds of additions and keeps rounding noise proportional to
+    it, different for every row.  On the second half of the columns, rows e and e + E/2 ("twins") are the same
+    N(0, sigma_w^2) draw, so twins tie exactly; every third twin then has the last mantissa bit of three entries
+    flipped, which turns its ties into gaps far below that noise, of either sign depending on the token.  Only numbers
+    are drawn here."""
+    assert H % 4 == 0 and E % 2 == 0
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 77])))
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    q, half = H // 4, H // 2
+    x[:, q:half] = x[:, :q]
+    xb = f32_to_bf16_bits(x)
+    w = np.zeros((E, H), dtype=np.float32)
+    base = (rng.standard_normal((E // 2, H - half)) * sigma_w).astype(np.float32)
+    w[:E // 2, half:] = base
+    w[E // 2:, half:] = base
+    wb = f32_to_bf16_bits(w)
+    a = f32_to_bf16_bits((rng.standard_normal((E, q)) * amp).astype(np.float32))
+    wb[:, :q] = a
+    wb[:, q:half] = a ^ np.uint16(0x8000)            # the same magnitude with the opposite sign
+    for e in range(E // 2, E, 3):
+        cols = half + rng.integers(0, H - half, 3)
+        wb[e, cols] = wb[e, cols] ^ np.uint16(1)
+    return xb, wb
 
 
 # ---- token log-probability / GRPO objective step --------------------------------------------------------

@@ -53,6 +53,12 @@ def test_each_entry_point_against_oracle(lib, oracle_lib, cfg):
     shp = shape_of(cfg)
     ws = moe.alloc_workspace(shp)
     o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+    # The named configurations are held to the absolute bound of 2e-2; the hand-made small shapes draw weights five
+    # times as large to exercise the tails, so their bound scales with the largest reference magnitude above 1.
+    named = cfg.name in wl.CONFIGS
+
+    def bound(ref, base=2e-2):
+        return base if named else base * max(1.0, np.abs(ref).max())
 
     # route
     idx, w = moe.moe_route_topk(shp, g["x"], g["w_router"], g["router_bias"], ws)
@@ -75,12 +81,12 @@ def test_each_entry_point_against_oracle(lib, oracle_lib, cfg):
     o_y = oracle_lib.grouped_swiglu(o_xp, o_off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
     y = moe.moe_grouped_swiglu(shp, to_dev(d["x"][o_r2a // cfg.K], cfg.dtype), torch.from_numpy(o_off).cuda(),
                                g["w_gate"], g["w_up"], g["w_down"], ws)
-    check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
+    check_close(host(y), o_y, "y_perm", max_abs=bound(o_y))
 
     # combine on the GPU's own y_perm against the same sum in double
     out = moe.moe_combine(shp, y, torch.from_numpy(o_a2r).cuda(), torch.from_numpy(o_w).cuda())
     o_out_of_gpu_y = oracle_lib.combine(host(y), o_a2r, o_w)
-    check_close(host(out), o_out_of_gpu_y, "combine", max_abs=1e-2 * max(1.0, np.abs(o_out_of_gpu_y).max()), rel_l2=4e-3)
+    check_close(host(out), o_out_of_gpu_y, "combine", max_abs=bound(o_out_of_gpu_y, 1e-2), rel_l2=4e-3)
 
     # fused forward against the oracle's forward
     o_out = oracle_lib.combine(o_y, o_a2r, o_w)
@@ -90,7 +96,7 @@ def test_each_entry_point_against_oracle(lib, oracle_lib, cfg):
                            topk_idx_out=idx2, topk_w_out=w2)
     assert np.array_equal(host(idx2), o_idx)
     check_weights(host(w2), o_w)
-    err, rel = check_close(host(out2), o_out, "forward", max_abs=2e-2 * max(1.0, np.abs(o_out).max()))
+    err, rel = check_close(host(out2), o_out, "forward", max_abs=bound(o_out))
     assert rel <= 6e-3      # what bf16 rounding of x, W, act, y and out should cost
     # forward without the optional outputs gives the same bits
     out3 = moe.moe_forward(shp, g["x"], g["w_router"], g["router_bias"], g["w_gate"], g["w_up"], g["w_down"], ws)
@@ -216,9 +222,10 @@ FULL = ["decode512", "skew4k", "prefill16k"]
 
 
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_forward_on_sampled_tokens(lib, oracle_lib, name):
-    """Full-size layer shapes: routing and permutation of every token are compared exactly; the block
-    output is compared on a seeded sample of tokens the oracle evaluates one by one."""
+def test_full_size_forward_every_element(lib, oracle_lib, name):
+    """Full-size layer shapes, in the launch configuration the benchmark times: routing ids, routing weights, offsets
+    and both permutation maps of every token are compared exactly, and EVERY element of the block output against the
+    oracle's forward pass, at the absolute bound of 2e-2 and relative L2 of 1e-2 (no scaling by the magnitude)."""
     cfg = wl.CONFIGS[name]
     d = wl.make_inputs(cfg)
     g = upload(cfg, d)
@@ -228,17 +235,35 @@ def test_full_size_forward_on_sampled_tokens(lib, oracle_lib, name):
     w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
     out = moe.moe_forward(shp, g["x"], g["w_router"], g["router_bias"], g["w_gate"], g["w_up"], g["w_down"], ws,
                           topk_idx_out=idx, topk_w_out=w)
-    o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+    o_out, o_idx, o_w = oracle_lib.forward(d["x_f32"], d["w_router_f32"], d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"],
+                                           cfg.K, bias=d["router_bias"], renormalize=cfg.renormalize)
     assert np.array_equal(host(idx), o_idx)
     check_weights(host(w), o_w)
+    o_off, o_r2a, o_a2r = oracle_lib.permute(o_idx, cfg.E)
     off, r2a, a2r, _ = moe.moe_permute(shp, idx, g["x"], ws, want_x_perm=False)
     assert np.array_equal(host(off), o_off) and np.array_equal(host(r2a), o_r2a) and np.array_equal(host(a2r), o_a2r)
-    rng = np.random.default_rng(123)
-    tok = np.unique(np.concatenate([[0, cfg.T - 1], rng.integers(0, cfg.T, 62)])).astype(np.int32)
-    # make sure the largest and the smallest non-empty expert are both covered
-    cnt = np.diff(o_off)
-    for e in (int(cnt.argmax()), int(np.where(cnt > 0, cnt, cnt.max() + 1).argmin())):
-        tok = np.append(tok, o_r2a[o_off[e + 1] - 1] // cfg.K).astype(np.int32)
-    ref = oracle_lib.forward_tokens(d["x_f32"], o_idx, o_w, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], tok)
-    check_close(host(out)[tok], ref, f"forward[{name}] sampled tokens")
-    assert np.all(np.isfinite(host(out)))
+    got = host(out)
+    err, rel = check_close(got, o_out, f"forward[{name}], all {cfg.T} tokens")
+    assert rel <= 6e-3
+    # no single token may be far off either (a wrong row would hide in the norm of 16384 good ones)
+    tok_rel = np.linalg.norm(got - o_out, axis=1) / np.linalg.norm(o_out, axis=1)
+    assert tok_rel.max() <= 2e-2, (int(tok_rel.argmax()), float(tok_rel.max()))
+
+
+def test_full_size_expert_rows_every_element(lib, oracle_lib):
+    """The grouped SwiGLU alone on the skewed batch (experts of a few rows next to experts of thousands, and empty
+    ones): every element of every expert-sorted output row against the oracle."""
+    cfg = wl.CONFIGS["skew4k"]
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+    o_xp = oracle_lib.gather_rows(d["x_f32"], o_r2a, cfg.K)
+    o_y = oracle_lib.grouped_swiglu(o_xp, o_off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
+    y = moe.moe_grouped_swiglu(shp, to_dev(d["x"][o_r2a // cfg.K], cfg.dtype), torch.from_numpy(o_off).cuda(),
+                               g["w_gate"], g["w_up"], g["w_down"], ws)
+    got = host(y)
+    check_close(got, o_y, "y_perm[skew4k], all rows")
+    row_rel = np.linalg.norm(got - o_y, axis=1) / np.maximum(np.linalg.norm(o_y, axis=1), 1e-30)
+    assert row_rel.max() <= 2e-2, (int(row_rel.argmax()), float(row_rel.max()))
