@@ -66,8 +66,8 @@ Workspace carve_workspace(const moe_shape_t &s, void *base) {
     take(cur, w.row_to_assign, sizeof(int32_t) * n);
     take(cur, w.assign_to_row, sizeof(int32_t) * n);
     take(cur, w.chunk_base, sizeof(int32_t) * nchunks * s.E);
-    // (expert, first row) pairs plus a count for the tiled kernel, or 32-byte entries of 256-row tiles in 8 per-XCD lists
-    take(cur, w.tile_map, std::max(sizeof(int32_t) * (2 * max_tiles + 4), (size_t)32 * (n / 256 + s.E + 8)));
+    // (expert, first row) pairs plus a count for the tiled kernel, or the large-batch kernel's 8 per-XCD lists
+    take(cur, w.tile_map, std::max(sizeof(int32_t) * (2 * max_tiles + 4), big_tile_list_bytes(s)));
     take(cur, w.act, sizeof(bf16_t) * n * s.I);
     void *y = nullptr;
     take(cur, y, elt_size(s) * n * s.H);

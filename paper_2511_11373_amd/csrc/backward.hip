@@ -24,7 +24,6 @@ hipError_t launch_bw_rows_kslow(const bf16_t *a0, const bf16_t *a1, const bf16_t
                                 const int32_t *tile_map, int max_tiles, bf16_t *out, int KD, int N, hipStream_t st);
 hipError_t launch_bw_wgrad(const bf16_t *P, const bf16_t *Q, const int32_t *off, int E, float *out, int M, int N, hipStream_t st);
 bool big_pre_activations_applicable(int H, int I);
-size_t big_tile_list_bytes(const moe_shape_t &s);
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st);
 hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, int row_div,
                                       const void *list, const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st);

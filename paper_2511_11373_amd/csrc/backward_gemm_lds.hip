@@ -333,7 +333,7 @@ bool bw_lds_applicable(const moe_shape_t &s) { return s.H % bwl::BK == 0 && s.I 
 hipError_t launch_bw_lds_rows(const moe_shape_t &s, const bf16_t *a0, const bf16_t *a1, const bf16_t *w0, const bf16_t *w1,
                               const void *list, const bf16_t *zeros, const int32_t *a0_token, bf16_t *out, int KD, int N,
                               hipStream_t st) {
-    const int max_tiles = s.T * s.K / bwl::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int tiles_per_xcd = big_tiles_per_xcd(s);
     const int nw = (N + bwl::BT - 1) / bwl::BT;
     hipLaunchKernelGGL((bwl::bw_lds_kernel<false, 0, bf16_t>), dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, a0, a1, w0, w1,
                        reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, (const int32_t *)nullptr, zeros, a0_token, (const int32_t *)nullptr, out, KD, 0, N, 0, nw, s.E,

@@ -12,6 +12,11 @@
 // position fetches the matching piece from global memory, so every 8 lanes still read one full
 // 128-byte line.
 //
+// A row tile that holds at most 128 rows (the tail of an expert, or an expert with few rows) takes a variant of the
+// main loop with a ring of three smaller LDS stages instead of two: it has a quarter of the arithmetic per stage or
+// less, so with two stages every stage would wait out a whole memory round trip; with three, two stages' loads
+// are in flight while one is multiplied, and such a tile costs little more than streaming its weights.
+//
 // Row tiles (expert, first row, end of the expert's rows) come from a list that a small kernel writes
 // once per call, already split per XCD: blocks are dealt round-robin to the 8 XCDs, block b is slot b/8
 // of XCD b%8, and XCD x owns a contiguous eighth of the row tiles, each with all its weight tiles, so
@@ -25,6 +30,9 @@ namespace big {
 constexpr int BW = 256, BT = 256, BK = 64;
 constexpr int ROWB = BK * 2;                  // bytes per LDS row
 constexpr int OPB = 256 * ROWB;               // bytes per operand stage (32 KB)
+constexpr int SHORT_ROWS = 128;               // row tiles of at most this many rows take the three-stage loop
+constexpr int SHORT_STAGE = OPB + SHORT_ROWS * ROWB;      // its stage: 256 weight rows + 128 token rows (48 KB)
+constexpr int LDS_BYTES = 3 * SHORT_STAGE;    // 144 KB; the two-stage loop uses the first 4 * OPB = 128 KB
 }  // namespace big
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -57,28 +65,15 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void *)p;
 }
 
-template <bool B>
-struct FullTile { static constexpr bool value = B; };
+// How a row tile is worked through: whole tiles take a branch-free loop; NX > 0 is the three-stage loop of short tiles,
+// which always loads NX token sub-tiles of 32 rows (so that the number of loads in flight is known to the waits).
+template <bool FULL, int NX>
+struct TileMode { static constexpr bool full = FULL; static constexpr int nx = NX; };
 
-// Which of the next stage's 16 global->LDS loads follows MFMA m of k step ks (-1: none).
-#ifndef MOE_BIG_LOADPLAN
-#define MOE_BIG_LOADPLAN 3
-#endif
-// Plans 0-2 load the next stage during the first k steps of the current one; plan 3 loads the stage after
-// the next during the last k step, right behind the barrier that frees the buffer, which leaves three k steps
-// for the data to arrive instead of one or two.
-__device__ constexpr int big_load_slot(int ks, int m) {
-#if MOE_BIG_LOADPLAN == 0
-    return ks == 0 ? m : -1;
-#elif MOE_BIG_LOADPLAN == 1
-    return (ks < 2 && m >= 8) ? ks * 8 + m - 8 : -1;
-#elif MOE_BIG_LOADPLAN == 2
-    return (ks < 2 && (m & 1)) ? ks * 8 + (m >> 1) : -1;
-#else
-    return ks == 3 ? m : -1;
-#endif
-}
-constexpr bool big_load_two_ahead = MOE_BIG_LOADPLAN == 3;
+// Which of the 16 global->LDS loads follows MFMA m of k step ks (-1: none).  The loads of the stage after the next are
+// issued during the last k step of the current one, right behind the barrier that frees the buffer they land in, which
+// leaves them three k steps to arrive (loading the next stage during the first k steps left one or two: 10 % slower).
+__device__ constexpr int big_load_slot(int ks, int m) { return ks == 3 ? m : -1; }
 
 // silu(g)*u with the hardware reciprocal (1 ulp): far inside the bf16 rounding that follows
 __device__ __forceinline__ float silu_mul_f(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
@@ -96,10 +91,8 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     int KD, int NW, int n_wtiles, int n_rows) {
     using namespace big;
     constexpr bool GATE_UP = MODE != kBigPlain;
-    __shared__ __attribute__((aligned(1024))) unsigned char WsA[OPB];
-    __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
-    __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
-    __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+    unsigned char *const WsA = lds, *const XsA = lds + OPB, *const WsB = lds + 2 * OPB, *const XsB = lds + 3 * OPB;
 
     // ---- which tile --------------------------------------------------------------------------
     // Slot s of an XCD falls into row tile s / n_wtiles of that XCD's list; the entry there describes the run of
@@ -201,9 +194,10 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     // that is not an MFMA only comes for free in the shadow of the MFMA issued just before it (the matrix
     // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and this k step's
     // share of the next stage's 16 global->LDS loads are therefore dealt out one per MFMA.
-    auto kstep = [&](auto full_c, int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wn,
+    auto kstep = [&](auto mode_c, int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wn,
                      unsigned char *Xn, int k_next) {
-        constexpr bool FULL = decltype(full_c)::value;
+        constexpr bool FULL = decltype(mode_c)::full;
+        constexpr int NX = decltype(mode_c)::nx;
         const int set = ks & 1;
         const unsigned wa = wrd + a_base + kpos[ks_rd], xa = xrd + b_base + kpos[ks_rd];
 #pragma unroll
@@ -218,7 +212,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
             }
             if (m < 8 && (FULL || read_live(m))) read_one(wa, xa, set ^ 1, m);
             const int j = big_load_slot(ks, m);
-            if (j >= 0 && (FULL || load_live(j))) issue(Wn, Xn, k_next, j);
+            if (j >= 0 && (FULL || (NX > 0 ? (!(j & 1) || (j >> 1) < NX) : load_live(j)))) issue(Wn, Xn, k_next, j);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -234,46 +228,89 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
     const int k_last = KD - BK;
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
+    auto run = [&](auto mode_c) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (load_live(j)) issue(WsA, XsA, 0, j);
-    if (big_load_two_ahead) {
+        for (int j = 0; j < 16; ++j)
+            if (load_live(j)) issue(WsA, XsA, 0, j);
 #pragma unroll
         for (int j = 0; j < 16; ++j)
             if (load_live(j)) issue(WsB, XsB, min(BK, k_last), j);
-        // a whole tile has 16 loads per stage in flight; a short one has fewer, how many is not known to the encoding
-        if (nsub == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        // a whole tile has 16 loads per stage in flight; a ragged one has fewer, how many is not known to the encoding
+        if (decltype(mode_c)::full) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         else MOE_WAIT_VMCNT(0);
-    } else {
-        MOE_WAIT_VMCNT(0);
-    }
-    __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-        if (read_live(q)) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
-    auto run = [&](auto full_c) {
+        for (int q = 0; q < 8; ++q)
+            if (read_live(q)) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
 #pragma unroll 1
         for (int kt = 0; kt < nk; ++kt) {
             const bool odd = kt & 1;
             const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
             const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
             // destination and k offset of the loads issued in this iteration
-            unsigned char *Wl = (odd != big_load_two_ahead) ? WsA : WsB, *Xl = (odd != big_load_two_ahead) ? XsA : XsB;
-            const int k_load = min((kt + (big_load_two_ahead ? 2 : 1)) * BK, k_last);
+            unsigned char *Wl = odd ? WsB : WsA, *Xl = odd ? XsB : XsA;
+            const int k_load = min((kt + 2) * BK, k_last);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(full_c, 0, wcur, xcur, 1, Wl, Xl, k_load);
+            kstep(mode_c, 0, wcur, xcur, 1, Wl, Xl, k_load);
             wait_lds_reads<0>(aop[1], bop[1]);
-            kstep(full_c, 1, wcur, xcur, 2, Wl, Xl, k_load);
+            kstep(mode_c, 1, wcur, xcur, 2, Wl, Xl, k_load);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(full_c, 2, wcur, xcur, 3, Wl, Xl, k_load);
+            kstep(mode_c, 2, wcur, xcur, 3, Wl, Xl, k_load);
             wait_lds_reads<0>(aop[1], bop[1]);
             MOE_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();
-            kstep(full_c, 3, wnxt, xnxt, 0, Wl, Xl, k_load);
+            kstep(mode_c, 3, wnxt, xnxt, 0, Wl, Xl, k_load);
         }
     };
-    if (nsub == 8) run(FullTile<true>{});
-    else run(FullTile<false>{});
+    // Short tiles: a ring of three stages (weights at the start of a stage, token rows behind them).  The loads of stage
+    // kt + 3 are issued during the last k step of stage kt into the buffer that stage just left, so two stages' loads
+    // are in flight while a stage is multiplied.  Every wave issues exactly 8 + NX loads per stage (token rows past the
+    // tile's end are other rows of the batch: loaded, multiplied into accumulators that are never stored), which is
+    // what lets the wait in front of the barrier name the number of loads that may still be under way.
+    auto run_short = [&](auto mode_c) {
+        constexpr int NL = 8 + decltype(mode_c)::nx;
+        unsigned char *p_cur = lds, *p_nxt = lds + SHORT_STAGE, *p_aft = lds + 2 * SHORT_STAGE;
+#pragma unroll
+        for (int st = 0; st < 3; ++st)
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (!(j & 1) || (j >> 1) < decltype(mode_c)::nx)
+                    issue(lds + st * SHORT_STAGE, lds + st * SHORT_STAGE + OPB, min(st * BK, k_last), j);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NL) : "memory");
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (read_live(q)) read_one(wsA + a_base + kpos[0], wsA + OPB + b_base + kpos[0], 0, q);
+#pragma unroll 1
+        for (int kt = 0; kt < nk; ++kt) {
+            const unsigned wcur = lds_addr(p_cur), xcur = wcur + OPB;
+            const unsigned wnxt = lds_addr(p_nxt), xnxt = wnxt + OPB;
+            const int k_load = min((kt + 3) * BK, k_last);
+            wait_lds_reads<0>(aop[0], bop[0]);
+            kstep(mode_c, 0, wcur, xcur, 1, p_cur, p_cur + OPB, k_load);
+            wait_lds_reads<0>(aop[1], bop[1]);
+            kstep(mode_c, 1, wcur, xcur, 2, p_cur, p_cur + OPB, k_load);
+            wait_lds_reads<0>(aop[0], bop[0]);
+            kstep(mode_c, 2, wcur, xcur, 3, p_cur, p_cur + OPB, k_load);
+            wait_lds_reads<0>(aop[1], bop[1]);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");      // stage kt + 1 has landed; kt + 2 may be under way
+            __builtin_amdgcn_s_barrier();
+            kstep(mode_c, 3, wnxt, xnxt, 0, p_cur, p_cur + OPB, k_load);
+            unsigned char *t = p_cur;
+            p_cur = p_nxt;
+            p_nxt = p_aft;
+            p_aft = t;
+        }
+    };
+    const int rows_here = row_end - row0;
+    if (rows_here > SHORT_ROWS) {
+        if (nsub == 8) run(TileMode<true, 0>{});
+        else run(TileMode<false, 0>{});
+    } else if (rows_here > 64) {
+        run_short(TileMode<false, 4>{});
+    } else {
+        run_short(TileMode<false, 2>{});
+    }
     wait_lds_reads<0>(aop[0], bop[0]);
     MOE_WAIT_VMCNT(0);
 
@@ -329,54 +366,78 @@ bool big_gemm_applicable(const moe_shape_t &s) {
 }
 
 // ---- per-XCD row-tile list ---------------------------------------------------------------------------
-// Two 16-byte words per row tile; XCD x owns row tiles [x*q, (x+1)*q) of the expert-ordered sequence, q = an
-// eighth of the tiles there are.  list[2*(x*tiles_per_xcd + i)] = (expert, first row of the expert, end of the
-// expert's rows, a) and the word after it (r, t0, 0, 0), where the expert's row tiles inside this XCD's share
-// are the r tiles starting at position a of the share, the first of them being tile t0 of the expert.
-// Expert = -1 past the end.  One block: tile counts per expert, their prefix sum, then one entry per thread and
-// step, its expert found by bisection in the prefix sums.
+// Two 16-byte words per row tile: list[2*(x*tiles_per_xcd + i)] = (expert, first row of the expert, end of the
+// expert's rows, i) and the word after it (1, t, 0, 0), t = the tile's index inside the expert; expert = -1 past the
+// end of an XCD's list.  (The first word's last field and the second word's first describe a run of consecutive row
+// tiles of one expert starting at position i; the lists written here only hold runs of one tile.)
+//
+// Row tiles come in two kinds: long ones (more than SHORT_ROWS rows; bound by the matrix cores) and short ones (the
+// tail of an expert or an expert with few rows; bound by streaming their weights).  A batch with skewed routing has
+// many of both, and an XCD that works through a stretch of short tiles alone cannot pull them from memory faster
+// than its own link allows while its matrix cores idle.  So each kind is dealt out evenly: XCD x gets a contiguous
+// eighth of the long tiles and a contiguous eighth of the short ones (both in expert order, so that the tiles
+// sharing an expert's weights still meet behind one L2), and inside an XCD's list the short tiles are spread
+// evenly among the long ones, so that at any time a few CUs stream while the rest multiply.
+// One block: tile counts per expert, their prefix sums, then one entry per thread and step, its expert found by
+// bisection in the prefix sums.
 __global__ __launch_bounds__(1024) void build_xcd_tile_list_kernel(const int32_t *__restrict__ off, int E,
                                                                    int tiles_per_xcd, i32x4 *__restrict__ list) {
-    __shared__ int first[kMaxExperts + 1];
-    for (int e = threadIdx.x; e < E; e += 1024) first[e] = (off[e + 1] - off[e] + big::BT - 1) / big::BT;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < E; ++e) { const int v = first[e]; first[e] = run; run += v; }
-        first[E] = run;
+    __shared__ int lfirst[kMaxExperts + 1], sfirst[kMaxExperts + 1];
+    for (int e = threadIdx.x; e < E; e += 1024) {
+        const int cnt = off[e + 1] - off[e], nt = (cnt + big::BT - 1) / big::BT;
+        const int tail_short = cnt > 0 && cnt - (nt - 1) * big::BT <= big::SHORT_ROWS;
+        lfirst[e] = nt - tail_short;
+        sfirst[e] = tail_short;
     }
     __syncthreads();
-    const int n_tiles = first[E], q = (n_tiles + 7) >> 3;      // q <= tiles_per_xcd by the launcher's bound on n_tiles
+    if (threadIdx.x == 0) {
+        int lrun = 0, srun = 0;
+        for (int e = 0; e < E; ++e) {
+            const int lv = lfirst[e], sv = sfirst[e];
+            lfirst[e] = lrun; sfirst[e] = srun;
+            lrun += lv; srun += sv;
+        }
+        lfirst[E] = lrun; sfirst[E] = srun;
+    }
+    __syncthreads();
+    const int n_long = lfirst[E], n_short = sfirst[E];
+    // XCD x takes tiles [x*q + min(x, r), ...) of a kind, q = N / 8, r = N % 8: shares differ by at most one tile
+    const int ql = n_long >> 3, rl = n_long & 7, qs = n_short >> 3, rs = n_short & 7;
     for (int idx = threadIdx.x; idx < 8 * tiles_per_xcd; idx += 1024) {
-        const int x = idx / tiles_per_xcd, i = idx - x * tiles_per_xcd, t = x * q + i;
+        const int x = idx / tiles_per_xcd, i = idx - x * tiles_per_xcd;
+        const int l0 = x * ql + min(x, rl), s0 = x * qs + min(x, rs);
+        const int nl = ql + (x < rl), ns = qs + (x < rs), tot = nl + ns;      // <= tiles_per_xcd by the launcher's bound
         i32x4 ea = {-1, 0, 0, 0}, eb = {1, 0, 0, 0};
-        if (i < q && t < n_tiles) {
-            int lo = 0, hi = E;                                 // last e with first[e] <= t (experts without rows repeat a value)
+        if (i < tot) {
+            // position i of the XCD's list holds a short tile when the running share of short tiles steps up there
+            const int s_before = (int)((long)i * ns / tot), is_short = (int)((long)(i + 1) * ns / tot) > s_before;
+            const int *first = is_short ? sfirst : lfirst;
+            const int t = is_short ? s0 + s_before : l0 + (i - s_before);
+            int lo = 0, hi = E;                                 // last e with first[e] <= t (experts without such tiles repeat a value)
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
                 if (first[mid] <= t) lo = mid; else hi = mid;
             }
-            const int share_end = min((x + 1) * q, n_tiles);
-            const int run_begin = max(first[lo], x * q), run_end = min(first[lo + 1], share_end);
-            ea = i32x4{lo, off[lo], off[lo + 1], run_begin - x * q};
-            eb = i32x4{run_end - run_begin, run_begin - first[lo], 0, 0};
+            const int n_long_e = lfirst[lo + 1] - lfirst[lo];
+            ea = i32x4{lo, off[lo], off[lo + 1], i};
+            eb = i32x4{1, is_short ? n_long_e : t - lfirst[lo], 0, 0};
         }
         list[2 * idx] = ea;
         list[2 * idx + 1] = eb;
     }
 }
 
-size_t big_tile_list_bytes(const moe_shape_t &s) {
-    const size_t max_tiles = (size_t)s.T * s.K / big::BT + s.E;
-    return 2 * 8 * ((max_tiles + 7) / 8) * sizeof(i32x4);
-}
+// Row tiles per XCD list: every expert ends with at most one partial tile, so there are at most T*K/BT + E row
+// tiles; an eighth of the long ones and an eighth of the short ones, each rounded up.
+int big_tiles_per_xcd(const moe_shape_t &s) { return (s.T * s.K / big::BT + s.E + 7) / 8 + 1; }
+
+size_t big_tile_list_bytes(const moe_shape_t &s) { return (size_t)2 * 8 * big_tiles_per_xcd(s) * sizeof(i32x4); }
 
 hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows, const int32_t *row_map,
                                      const int32_t *off, const bf16_t *wg, const bf16_t *wu, const bf16_t *wd,
                                      bf16_t *act, int32_t *tile_map, bf16_t *y_perm, hipStream_t st, Probe *probe) {
     using namespace big;
-    // every expert ends with at most one partial tile, so there are at most T*K/BT + E row tiles
-    const int max_tiles = s.T * s.K / BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int tiles_per_xcd = big_tiles_per_xcd(s);
     i32x4 *list = reinterpret_cast<i32x4 *>(tile_map);
     hipLaunchKernelGGL(build_xcd_tile_list_kernel, dim3(1), dim3(1024), 0, st, off, s.E, tiles_per_xcd, list);
     hipError_t err = hipGetLastError();
@@ -400,7 +461,7 @@ hipError_t launch_grouped_swiglu_big(const moe_shape_t &s, const bf16_t *x_rows,
 bool big_pre_activations_applicable(int H, int I) { return H % big::BK == 0 && I % (big::BW / 2) == 0; }
 
 hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *list, hipStream_t st) {
-    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int tiles_per_xcd = big_tiles_per_xcd(s);
     hipLaunchKernelGGL(build_xcd_tile_list_kernel, dim3(1), dim3(1024), 0, st, off, s.E, tiles_per_xcd, reinterpret_cast<i32x4 *>(list));
     return hipGetLastError();
 }
@@ -409,7 +470,7 @@ hipError_t launch_big_tile_list(const moe_shape_t &s, const int32_t *off, void *
 // pass's row -> assignment map)
 hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, const int32_t *row_token, int row_div,
                                       const void *list, const bf16_t *wg, const bf16_t *wu, bf16_t *g, bf16_t *u, hipStream_t st) {
-    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int tiles_per_xcd = big_tiles_per_xcd(s);
     const int nw = s.I / (big::BW / 2);
     hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigGateUpRaw>, dim3(8 * tiles_per_xcd * nw), dim3(256), 0, st, rows, row_token,
                        row_div, reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wg, wu, g, u, s.H, s.I, nw, s.T * s.K);
@@ -421,7 +482,7 @@ hipError_t launch_big_pre_activations(const moe_shape_t &s, const bf16_t *rows, 
 bool big_down_applicable(int H, int I) { return H % big::BW == 0 && I % big::BK == 0; }
 hipError_t launch_big_down(const moe_shape_t &s, const bf16_t *act, const void *list, const bf16_t *wd, bf16_t *y_perm,
                            hipStream_t st) {
-    const int max_tiles = s.T * s.K / big::BT + s.E, tiles_per_xcd = (max_tiles + 7) / 8;
+    const int tiles_per_xcd = big_tiles_per_xcd(s);
     const int nw2 = s.H / big::BW;
     hipLaunchKernelGGL(grouped_gemm_big_kernel<kBigPlain>, dim3(8 * tiles_per_xcd * nw2), dim3(256), 0, st, act,
                        (const int32_t *)nullptr, 1, reinterpret_cast<const i32x4 *>(list), tiles_per_xcd, wd, wd, y_perm,

@@ -63,6 +63,10 @@ constexpr int kMinTokenTile = 16;      // smallest row tile any GEMM variant use
 
 Workspace carve_workspace(const moe_shape_t &s, void *base);
 
+// row-tile lists of the large-batch grouped GEMM (8 lists, one per XCD, of big_tiles_per_xcd entries of 32 bytes)
+int big_tiles_per_xcd(const moe_shape_t &s);
+size_t big_tile_list_bytes(const moe_shape_t &s);
+
 int router_ksplit(const moe_shape_t &s);
 size_t router_scratch_bytes(const moe_shape_t &s);
 
