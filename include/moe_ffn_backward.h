@@ -9,6 +9,8 @@
  *
  *   out_t = sum_k w_k y_k               dw_k  = <d_out_t, y_k>
  *   w = softmax(l over the selection)   dl_k  = w_k (dw_k - sum_j w_j dw_j)
+ *   (renormalize == 0: w_k = p_{e_k}, p the softmax over all E logits, and every logit of the token has a gradient,
+ *    dl_e = p_e ([e selected] dw_e - sum_j w_j dw_j); the three router sums below then run over all experts / tokens)
  *   l_e = <x_t, Wr_e> + b_e             dx_t += sum_k dl_k Wr_e;  dWr_e += dl x_t;  db_e += dl
  *   y = Wd a, a = silu(g) u             da = w_k Wd^T d_out_t;  dWd_e += (w_k d_out_t) a^T
  *   g = Wg x, u = Wu x                  dg = da u silu'(g), du = da silu(g), silu'(g) = s (1 + g (1 - s)), s = 1/(1+e^-g)
@@ -17,8 +19,10 @@
  * Conventions: those of moe_ffn.h (device pointers unless marked host, dense row-major tensors, caller-owned
  * buffers and stream, nothing allocated or kept, arguments validated on the host before anything is enqueued,
  * every data pointer 16-byte aligned, outputs overwritten in full, T == 0 gives zero weight gradients).
- * Restrictions of this pass: shape->dtype must be MOE_BF16 (else MOE_ERR_DTYPE) and shape->renormalize must be
- * nonzero (else MOE_ERR_SHAPE).  x, the weights, d_out, d_x and the row gradients are bf16; every weight
+ * Restriction of this pass: shape->dtype must be MOE_BF16 (else MOE_ERR_DTYPE).  Both kinds of routing weights are
+ * taken (shape->renormalize); the un-renormalised kind needs T*E more floats of workspace and its router gradients are
+ * plain dense sums (not tuned: it is not the configuration of the model the paper trains).
+ * x, the weights, d_out, d_x and the row gradients are bf16; every weight
  * gradient is float and is written, not accumulated into (an expert that received no row gets zeros).
  * Nothing is kept from a forward call: routing, permutation and the expert pre-activations are recomputed (what
  * activation recomputation does for long sequences).  The pair moe_forward_saving / moe_backward_saved is the other

@@ -98,10 +98,32 @@ __global__ __launch_bounds__(256) void bw_softmax_kernel(const float *__restrict
     }
 }
 
+// Un-renormalised routing weights (w_k = p_{e_k}, p the softmax over all E logits): every logit of a token receives a
+// gradient, dl_e = p_e ([e selected] dw_e - sum_k w_k dw_k).  One thread per token; probs [T][E] is overwritten by dl.
+__global__ __launch_bounds__(256) void bw_softmax_dense_kernel(const float *__restrict__ topk_w, const float *__restrict__ dw_row,
+                                                               const int32_t *__restrict__ assign_to_row,
+                                                               const int32_t *__restrict__ topk_idx, float *__restrict__ probs,
+                                                               int T, int K, int E) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    float mean = 0.f;
+    for (int k = 0; k < K; ++k) mean = fmaf(topk_w[(size_t)t * K + k], dw_row[assign_to_row[(size_t)t * K + k]], mean);
+    float *p = probs + (size_t)t * E;
+    for (int e = 0; e < E; ++e) p[e] = -p[e] * mean;
+    // the selected experts' extra term, with their probability taken from the routing weights (the same number)
+    for (int k = 0; k < K; ++k) {
+        const size_t a = (size_t)t * K + k;
+        p[topk_idx[a]] = fmaf(topk_w[a], dw_row[assign_to_row[a]], p[topk_idx[a]]);
+    }
+}
+
 // One block per token: dx_t = sum_k dxp[row(t,k)] + sum_k dl_k Wr[e_k], float sums in k order, rounded once.
+// With dl_full (un-renormalised weights) the router term runs over all E experts, coefficients dl_full[t][e], instead of
+// the K selected ones.
 __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ dxp, const int32_t *__restrict__ assign_to_row,
                                                     const float *__restrict__ dl, const int32_t *__restrict__ topk_idx,
-                                                    const bf16_t *__restrict__ wr, bf16_t *__restrict__ dx, int H, int K) {
+                                                    const bf16_t *__restrict__ wr, bf16_t *__restrict__ dx, int H, int K,
+                                                    const float *__restrict__ dl_full, int E) {
     const int t = blockIdx.x;
     for (int p = threadIdx.x; p < (H >> 3); p += 256) {
         float acc[8];
@@ -121,6 +143,10 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
                 e[i] = topk_idx[a];
                 c[i] = ok ? dl[a] : 0.f;
                 live[i] = ok ? 1.f : 0.f;
+            }
+            if (dl_full) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { e[i] = 0; c[i] = 0.f; }      // the router term follows below, over all experts
             }
             u32x4 v[8], r[8];
 #pragma unroll
@@ -142,6 +168,25 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
                     acc[2 * j + 1] = fmaf(c[i], __uint_as_float(r[i][j] & 0xFFFF0000u), acc[2 * j + 1]);
                 }
         }
+        if (dl_full) {
+            for (int e0 = 0; e0 < E; e0 += 8) {
+                float c[8];
+                u32x4 r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int e = min(e0 + i, E - 1);
+                    c[i] = e0 + i < E ? dl_full[(size_t)t * E + e] : 0.f;
+                    r[i] = *reinterpret_cast<const u32x4 *>(wr + (size_t)e * H + p * 8);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acc[2 * j] = fmaf(c[i], __uint_as_float(r[i][j] << 16), acc[2 * j]);
+                        acc[2 * j + 1] = fmaf(c[i], __uint_as_float(r[i][j] & 0xFFFF0000u), acc[2 * j + 1]);
+                    }
+            }
+        }
         *reinterpret_cast<u32x4 *>(dx + (size_t)t * H + p * 8) =
             u32x4{pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7])};
     }
@@ -150,14 +195,18 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const bf16_t *__restrict__ d
 // Router weight gradient: dWr[e][h] = sum over the rows r of expert e of dl_row[r] x_perm[r][h] (x_perm[r] = x[row_token[r]] with a map).  Block (e, 512-wide slice
 // of h), 4 waves: wave w sums rows r0 + w, r0 + w + 4, ... in that order, four rows in flight, and the four partial sums are
 // added in wave order, so the result does not depend on timing.
+// With off == nullptr (un-renormalised weights: every token has a logit gradient for every expert) the rows are all T
+// tokens of x itself and the coefficient of row t is dl_row[t * coef_stride + e].
 __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__restrict__ x_perm, const int32_t *__restrict__ row_token,
                                                               const float *__restrict__ dl_row, const int32_t *__restrict__ off,
-                                                              float *__restrict__ dwr, float *__restrict__ dbias, int H) {
+                                                              float *__restrict__ dwr, float *__restrict__ dbias, int H,
+                                                              int n_all, int coef_stride) {
     __shared__ float part[4][64][9];
     const int e = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int h0 = blockIdx.y * 512 + lane * 8;
     const bool live = h0 < H;
-    const int r0 = off[e], r1 = off[e + 1];
+    const int r0 = off ? off[e] : 0, r1 = off ? off[e + 1] : n_all;
+    if (!off) dl_row += e;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
@@ -176,14 +225,15 @@ __global__ __launch_bounds__(256) void bw_router_wgrad_kernel(const bf16_t *__re
     auto row_at = [&](int r) { return live ? *reinterpret_cast<const u32x4 *>(x_perm + row_of(r) * H + h0) : zero; };
     int r = r0 + wave;
     for (; r + 12 < r1; r += 16) {          // four rows in flight per wave: the loop is a chain of memory round trips
-        const float c0 = dl_row[r], c1 = dl_row[r + 4], c2 = dl_row[r + 8], c3 = dl_row[r + 12];
+        const float c0 = dl_row[(size_t)r * coef_stride], c1 = dl_row[(size_t)(r + 4) * coef_stride],
+                    c2 = dl_row[(size_t)(r + 8) * coef_stride], c3 = dl_row[(size_t)(r + 12) * coef_stride];
         const u32x4 v0 = row_at(r), v1 = row_at(r + 4), v2 = row_at(r + 8), v3 = row_at(r + 12);
         add(c0, v0);
         add(c1, v1);
         add(c2, v2);
         add(c3, v3);
     }
-    for (; r < r1; r += 4) add(dl_row[r], row_at(r));
+    for (; r < r1; r += 4) add(dl_row[(size_t)r * coef_stride], row_at(r));
 #pragma unroll
     for (int j = 0; j < 8; ++j) part[wave][lane][j] = acc[j];
     part[wave][lane][8] = bsum;
@@ -235,6 +285,7 @@ struct BwWorkspace {
     void *big_list;                     // per-XCD row-tile list of the forward pass's large-batch GEMM
     bf16_t *zeros;                      // 512 zero bytes: what the large-batch GEMMs read past an expert's last row
     int32_t *row_token;                 // [n]: the token each expert-sorted row belongs to
+    float *probs;                       // [T][E], un-renormalised weights only: the full softmax, later every logit's gradient
     size_t total;
 };
 
@@ -259,6 +310,7 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.big_list, big_tile_list_bytes(s));
     take(b.zeros, 512);
     take(b.row_token, n * 4);
+    take(b.probs, s.renormalize ? 0 : (size_t)s.T * s.E * 4);
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
     return b;
 }
@@ -271,7 +323,6 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
     if ((s->H & 7) || (s->I & 7)) return MOE_ERR_SHAPE;
     if ((long long)s->T * s->K > 0x7FFFFFFFLL || (long long)s->T * s->E > 0x7FFFFFFFLL) return MOE_ERR_SHAPE;
     if (s->dtype != MOE_BF16) return MOE_ERR_DTYPE;          // the backward pass is written for bf16 storage
-    if (!s->renormalize) return MOE_ERR_SHAPE;               // ... and for weights renormalised over the selection
     return MOE_OK;
 }
 
@@ -427,7 +478,12 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     const bool routed = topk_idx_saved && topk_w_saved;
     const int32_t *topk_idx = routed ? topk_idx_saved : w.topk_idx;
     const float *topk_w = routed ? topk_w_saved : w.topk_w;
-    if (!routed && launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess) return MOE_ERR_HIP;
+    // Un-renormalised weights need the softmax over all experts: the router runs even when the routing was handed over
+    // (its partial logit sums are what the probabilities are computed from).
+    const bool dense = !s.renormalize;
+    if ((!routed || dense) && launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess)
+        return MOE_ERR_HIP;
+    if (dense && launch_router_probs(s, w.logit_part, router_bias, b.probs, hs) != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);
     if (launch_permute(s, topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
@@ -450,14 +506,27 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
                         (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe,
                         (const bf16_t *)g_rows, (const bf16_t *)u_rows) != hipSuccess)
         return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
-    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, topk_idx, (const bf16_t *)w_router,
-                       (bf16_t *)d_x, s.H, s.K);
-    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, x_rows, row_token, b.dw_row, w.expert_offsets,
-                       d_w_router, d_router_bias, s.H);
-    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    if (dense) {
+        hipLaunchKernelGGL(bw_softmax_dense_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, topk_w, b.dw_row, w.assign_to_row, topk_idx,
+                           b.probs, s.T, s.K, s.E);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+        hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, topk_idx, (const bf16_t *)w_router,
+                           (bf16_t *)d_x, s.H, s.K, b.probs, s.E);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+        // every token contributes to every expert's router row: the sums run over the tokens of x in token order
+        hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, (const bf16_t *)x, (const int32_t *)nullptr,
+                           b.probs, (const int32_t *)nullptr, d_w_router, d_router_bias, s.H, s.T, s.E);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    } else {
+        hipLaunchKernelGGL(bw_softmax_kernel, dim3((s.T + 255) / 256), dim3(256), 0, hs, topk_w, b.dw_row, w.assign_to_row, b.dl, s.T, s.K);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+        hipLaunchKernelGGL(bw_dx_kernel, dim3(s.T), dim3(256), 0, hs, dxp, w.assign_to_row, b.dl, topk_idx, (const bf16_t *)w_router,
+                           (bf16_t *)d_x, s.H, s.K, (const float *)nullptr, s.E);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+        hipLaunchKernelGGL(bw_router_wgrad_kernel, dim3(s.E, (s.H + 511) / 512), dim3(256), 0, hs, x_rows, row_token, b.dw_row, w.expert_offsets,
+                           d_w_router, d_router_bias, s.H, 0, 1);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    }
     bw_mark(probe);
     bw_mark(probe);       // closes the empty calibration interval
     return MOE_OK;

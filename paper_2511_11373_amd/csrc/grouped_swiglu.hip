@@ -279,7 +279,10 @@ static hipError_t launch_typed(const moe_shape_t &s, const S *x_rows, const int3
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     probe_mark(probe);
-    hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MW, MT, kBK>), dim3(max_tiles, (s.H + BW - 1) / BW),
+    // the down pass takes 128 weight rows per block (two MFMA tiles per wave): its rows are short (I elements), so a block of
+    // 64 rows streams too little between start-up and epilogue (512 tokens at H 2048, I 768: 91 -> 84 us)
+    constexpr int MWD = 2, BWD = WW * MWD * 32;
+    hipLaunchKernelGGL((grouped_gemm_kernel<bf16_t, S, S, false, WW, WT, MWD, MT, kBK>), dim3(max_tiles, (s.H + BWD - 1) / BWD),
                        dim3(WW * WT * 64), 0, st, (const bf16_t *)act, (const int32_t *)nullptr, 1, off, tile_map,
                        max_tiles, wd, wd, y_perm, s.I, s.H);
     return hipGetLastError();

@@ -83,6 +83,8 @@ inline void probe_mark(Probe *p) { if (p) p->mark(); }
 hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_router, const float *bias,
                         double *logit_part, int32_t *topk_idx, float *topk_w, hipStream_t st,
                         Probe *probe = nullptr);
+// p[t][e] = softmax over all E logits, from the partial sums launch_route left in logit_part (renormalize == 0 only)
+hipError_t launch_router_probs(const moe_shape_t &s, const double *logit_part, const float *bias, float *probs, hipStream_t st);
 // One-block permutation is used for batches of at most 16 chunks; it can also emit the GEMM's row-tile
 // list (tile_rows > 0), which saves a launch.  Returns whether `s` takes that path.
 inline bool permute_is_small(const moe_shape_t &s) { return (long)s.T * s.K <= 16L * kPermChunk; }

@@ -549,6 +549,31 @@ __global__ __launch_bounds__(256, 4) void router_fast_select_kernel(const bf16_t
     write_weights(sel, K, 1, 0.f, topk_w + (size_t)t * K, lane);
 }
 
+// Full softmax over all E logits of a token, p[t][e] = exp(l_e - max) / sum, from the partial logit sums the fp64 path
+// leaves behind (the backward pass of un-renormalised routing weights needs every expert's probability).  One wave per token.
+__global__ __launch_bounds__(256) void router_probs_kernel(const double *__restrict__ part, int ksplit, const float *__restrict__ bias,
+                                                           float *__restrict__ probs, int T, int E) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= T) return;
+    float m = -3.0e38f;
+    for (int e = lane; e < E; e += 64) m = fmaxf(m, final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    float z = 0.f;
+    for (int e = lane; e < E; e += 64) z += expf(final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e) - m);
+    z = wave_sum_f32(z);
+    for (int e = lane; e < E; e += 64)
+        probs[(size_t)t * E + e] = expf(final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e) - m) / z;
+}
+
+// Only after launch_route on the same shape and workspace, and only for shapes that take the fp64 path (every shape with
+// renormalize == 0 does).
+hipError_t launch_router_probs(const moe_shape_t &s, const double *logit_part, const float *bias, float *probs, hipStream_t st) {
+    hipLaunchKernelGGL(router_probs_kernel, dim3((s.T + 3) / 4), dim3(256), 0, st, logit_part, router_ksplit(s), bias, probs, s.T, s.E);
+    return hipGetLastError();
+}
+
 static bool router_fast_applicable(const moe_shape_t &s) {
     // one block works through 16 tokens for tens of microseconds, so the path pays off only when there are
     // enough blocks to fill the chip several times; small batches keep the two-kernel fp64 path
