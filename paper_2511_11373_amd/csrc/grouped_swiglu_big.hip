@@ -32,7 +32,7 @@ constexpr int ROWB = BK * 2;                  // bytes per LDS row
 constexpr int OPB = 256 * ROWB;               // bytes per operand stage (32 KB)
 constexpr int SHORT_ROWS = 128;               // row tiles of at most this many rows take the three-stage loop
 constexpr int SHORT_STAGE = OPB + SHORT_ROWS * ROWB;      // its stage: 256 weight rows + 128 token rows (48 KB)
-constexpr int LDS_BYTES = 3 * SHORT_STAGE;    // 144 KB; the two-stage loop uses the first 4 * OPB = 128 KB
+constexpr int LDS_BYTES = 5 * OPB;            // 160 KB: three weight stages and two token stages of long tiles (3 * SHORT_STAGE fits too)
 }  // namespace big
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -70,11 +70,6 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
 template <bool FULL, int NX>
 struct TileMode { static constexpr bool full = FULL; static constexpr int nx = NX; };
 
-// Which of the 16 global->LDS loads follows MFMA m of k step ks (-1: none).  The loads of the stage after the next are
-// issued during the last k step of the current one, right behind the barrier that frees the buffer they land in, which
-// leaves them three k steps to arrive (loading the next stage during the first k steps left one or two: 10 % slower).
-__device__ constexpr int big_load_slot(int ks, int m) { return ks == 3 ? m : -1; }
-
 // silu(g)*u with the hardware reciprocal (1 ulp): far inside the bf16 rounding that follows
 __device__ __forceinline__ float silu_mul_f(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
 
@@ -92,7 +87,6 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     using namespace big;
     constexpr bool GATE_UP = MODE != kBigPlain;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
-    unsigned char *const WsA = lds, *const XsA = lds + OPB, *const WsB = lds + 2 * OPB, *const XsB = lds + 3 * OPB;
 
     // ---- which tile --------------------------------------------------------------------------
     // Slot s of an XCD falls into row tile s / n_wtiles of that XCD's list; the entry there describes the run of
@@ -186,16 +180,15 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
             default: bop[set][3] = lds_read_b128<192 * ROWB>(xa); break;
         }
     };
-    // A short (ragged) tile skips what only its missing token sub-tiles would use: their loads (token load i fills
-    // sub-tile i) and the operand reads of token sub-tiles this wave does not multiply; a wave left without any reads nothing.
-    auto load_live = [&](int j) { return !(j & 1) || (j >> 1) < nsub; };
+    // A ragged tile skips the operand reads and the products of token sub-tiles it does not have; a wave left without any
+    // reads nothing.  (The loads are issued all the same, so that the number in flight is known.)
     auto read_live = [&](int q) { return q == 5 ? nb > 1 : q == 6 ? nb > 2 : q == 7 ? nb > 3 : nb > 0; };
     // One 16-wide k step: 16 MFMAs out of operand set ks&1.  A wave is alone on its SIMD, so an instruction
     // that is not an MFMA only comes for free in the shadow of the MFMA issued just before it (the matrix
-    // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and this k step's
-    // share of the next stage's 16 global->LDS loads are therefore dealt out one per MFMA.
+    // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and, in a stage's last
+    // k step, the 16 global->LDS loads are therefore dealt out one per MFMA.
     auto kstep = [&](auto mode_c, int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wn,
-                     unsigned char *Xn, int k_next) {
+                     unsigned char *Xn, int k_w, int k_x) {
         constexpr bool FULL = decltype(mode_c)::full;
         constexpr int NX = decltype(mode_c)::nx;
         const int set = ks & 1;
@@ -211,55 +204,65 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                     acc[a2][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a2], bop[set][b], acc[a2][b], 0, 0, 0);
             }
             if (m < 8 && (FULL || read_live(m))) read_one(wa, xa, set ^ 1, m);
-            const int j = big_load_slot(ks, m);
-            if (j >= 0 && (FULL || (NX > 0 ? (!(j & 1) || (j >> 1) < NX) : load_live(j)))) issue(Wn, Xn, k_next, j);
+            if (ks == 3) {
+                // long tiles: the 8 token loads first, then the 8 weight loads (the wait in front of the next barrier lets
+                // exactly the weight loads stay under way); short tiles: weight and token loads alternate
+                const int j = NX > 0 ? m : (m < 8 ? 2 * m + 1 : 2 * (m - 8));
+                if (NX == 0 || !(j & 1) || (j >> 1) < NX) issue(Wn, Xn, (j & 1) ? k_x : k_w, j);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // ---- main loop ------------------------------------------------------------------------------------
-    // Two LDS stages, one block barrier per stage.  Operand registers are double-buffered per 16-wide k step.
-    // The barrier sits in front of the last k step of a stage: by then this wave has read everything it needs
-    // from the current buffer and its own loads into the other buffer have landed, so behind the barrier the
-    // current buffer is free in every wave and the other one is complete.  The last k step therefore reads the
-    // first operands of the next stage and issues the 16 loads of the stage after the next into the buffer
-    // just freed; they have the three following k steps (about a microsecond) to arrive, which is what a miss
-    // to HBM takes under load.  The last two stages reload the final k tile instead of branching around the loads.
+    // One block barrier per 64-wide stage.  Operand registers are double-buffered per 16-wide k step.  The barrier sits
+    // in front of the last k step of a stage: by then this wave has read everything it needs from the current buffers
+    // and its own loads of the next stage have landed, so behind the barrier the current buffers are free in every wave
+    // and the next ones complete.  The last k step therefore reads the first operands of the next stage and issues
+    // loads into the buffers just freed.
+    // Long tiles keep the weights in a ring of three stages and the token rows in a ring of two: the token rows of the
+    // stage after the next are issued there (three k steps to arrive: they come from L2 or the last-level cache, each
+    // row being read by 48 blocks) and the WEIGHTS of the stage after that, which therefore have a whole stage more,
+    // seven k steps, to arrive - a weight tile is read by four blocks only and often comes from HBM.  The last stages
+    // reload the final k tile instead of branching around the loads.  Every wave issues all 16 loads of a stage, live
+    // token rows or not (rows past the tile's end are other rows of the batch), so the waits can count.
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
     const int k_last = KD - BK;
-    const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
+    const unsigned wsA = lds_addr(lds);
+    auto all_loads = [&](unsigned char *Ws, unsigned char *Xs, int k0, int kind) {      // kind 0: weights, 1: token rows
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue(Ws, Xs, k0, 2 * i + kind);
+    };
     auto run = [&](auto mode_c) {
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (load_live(j)) issue(WsA, XsA, 0, j);
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (load_live(j)) issue(WsB, XsB, min(BK, k_last), j);
-        // a whole tile has 16 loads per stage in flight; a ragged one has fewer, how many is not known to the encoding
-        if (decltype(mode_c)::full) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else MOE_WAIT_VMCNT(0);
+        unsigned char *w_cur = lds, *w_nxt = lds + OPB, *w_aft = lds + 2 * OPB;
+        unsigned char *x_cur = lds + 3 * OPB, *x_nxt = lds + 4 * OPB;
+        all_loads(w_cur, x_cur, 0, 0);
+        all_loads(w_cur, x_cur, 0, 1);
+        all_loads(w_nxt, x_nxt, min(BK, k_last), 0);
+        all_loads(w_nxt, x_nxt, min(BK, k_last), 1);
+        all_loads(w_aft, x_cur, min(2 * BK, k_last), 0);
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // stage 0 has landed
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-            if (read_live(q)) read_one(wsA + a_base + kpos[0], xsA + b_base + kpos[0], 0, q);
+            if (read_live(q)) read_one(lds_addr(w_cur) + a_base + kpos[0], lds_addr(x_cur) + b_base + kpos[0], 0, q);
 #pragma unroll 1
         for (int kt = 0; kt < nk; ++kt) {
-            const bool odd = kt & 1;
-            const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
-            const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
-            // destination and k offset of the loads issued in this iteration
-            unsigned char *Wl = odd ? WsB : WsA, *Xl = odd ? XsB : XsA;
-            const int k_load = min((kt + 2) * BK, k_last);
+            const unsigned wcur = lds_addr(w_cur), xcur = lds_addr(x_cur), wnxt = lds_addr(w_nxt), xnxt = lds_addr(x_nxt);
+            const int k_w = min((kt + 3) * BK, k_last), k_x = min((kt + 2) * BK, k_last);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(mode_c, 0, wcur, xcur, 1, Wl, Xl, k_load);
+            kstep(mode_c, 0, wcur, xcur, 1, w_cur, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[1], bop[1]);
-            kstep(mode_c, 1, wcur, xcur, 2, Wl, Xl, k_load);
+            kstep(mode_c, 1, wcur, xcur, 2, w_cur, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(mode_c, 2, wcur, xcur, 3, Wl, Xl, k_load);
+            kstep(mode_c, 2, wcur, xcur, 3, w_cur, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[1], bop[1]);
-            MOE_WAIT_VMCNT(0);
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");      // all but the newest weight stage has landed
             __builtin_amdgcn_s_barrier();
-            kstep(mode_c, 3, wnxt, xnxt, 0, Wl, Xl, k_load);
+            kstep(mode_c, 3, wnxt, xnxt, 0, w_cur, x_cur, k_w, k_x);
+            unsigned char *t = w_cur;
+            w_cur = w_nxt; w_nxt = w_aft; w_aft = t;
+            t = x_cur; x_cur = x_nxt; x_nxt = t;
         }
     };
     // Short tiles: a ring of three stages (weights at the start of a stage, token rows behind them).  The loads of stage
@@ -287,15 +290,15 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
             const unsigned wnxt = lds_addr(p_nxt), xnxt = wnxt + OPB;
             const int k_load = min((kt + 3) * BK, k_last);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(mode_c, 0, wcur, xcur, 1, p_cur, p_cur + OPB, k_load);
+            kstep(mode_c, 0, wcur, xcur, 1, p_cur, p_cur + OPB, k_load, k_load);
             wait_lds_reads<0>(aop[1], bop[1]);
-            kstep(mode_c, 1, wcur, xcur, 2, p_cur, p_cur + OPB, k_load);
+            kstep(mode_c, 1, wcur, xcur, 2, p_cur, p_cur + OPB, k_load, k_load);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(mode_c, 2, wcur, xcur, 3, p_cur, p_cur + OPB, k_load);
+            kstep(mode_c, 2, wcur, xcur, 3, p_cur, p_cur + OPB, k_load, k_load);
             wait_lds_reads<0>(aop[1], bop[1]);
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");      // stage kt + 1 has landed; kt + 2 may be under way
             __builtin_amdgcn_s_barrier();
-            kstep(mode_c, 3, wnxt, xnxt, 0, p_cur, p_cur + OPB, k_load);
+            kstep(mode_c, 3, wnxt, xnxt, 0, p_cur, p_cur + OPB, k_load, k_load);
             unsigned char *t = p_cur;
             p_cur = p_nxt;
             p_nxt = p_aft;
