@@ -19,11 +19,14 @@
  * Conventions: those of moe_ffn.h (device pointers unless marked host, dense row-major tensors, caller-owned
  * buffers and stream, nothing allocated or kept, arguments validated on the host before anything is enqueued,
  * every data pointer 16-byte aligned, outputs overwritten in full, T == 0 gives zero weight gradients).
- * Restriction of this pass: shape->dtype must be MOE_BF16 (else MOE_ERR_DTYPE).  Both kinds of routing weights are
- * taken (shape->renormalize); the un-renormalised kind needs T*E more floats of workspace and its router gradients are
- * plain dense sums (not tuned: it is not the configuration of the model the paper trains).
- * x, the weights, d_out, d_x and the row gradients are bf16; every weight
- * gradient is float and is written, not accumulated into (an expert that received no row gets zeros).
+ * Storage types: shape->dtype names the type of x, the weights, d_out, d_x and the row gradients, as in moe_ffn.h.  The
+ * GEMMs multiply bf16 either way: with MOE_F32 the router still reads the float values (it has to select what the forward
+ * pass selected), every other input is rounded once to bf16 into the workspace (which grows by those copies) and d_x is
+ * widened on the way out.  moe_forward_saving / moe_backward_saved are MOE_BF16 only (else MOE_ERR_DTYPE).
+ * Both kinds of routing weights are taken (shape->renormalize); the un-renormalised kind needs T*E more floats of
+ * workspace and its router gradients are plain dense sums (not tuned: it is not the configuration of the model the
+ * paper trains).  Every weight gradient is float and is written, not accumulated into (an expert that received no row
+ * gets zeros).
  * Nothing is kept from a forward call: routing, permutation and the expert pre-activations are recomputed (what
  * activation recomputation does for long sequences).  The pair moe_forward_saving / moe_backward_saved is the other
  * choice: the forward pass keeps the pre-activations g and u of every expert-sorted row, the backward pass reads them.
@@ -43,9 +46,9 @@ moe_status_t moe_backward_workspace_bytes(const moe_shape_t *shape, size_t *out_
 
 /*
  * Backward of moe_grouped_swiglu over expert-sorted rows (the data- and weight-gradient grouped GEMMs).
- *   x_perm   [T*K,H] bf16     expert_offsets [E+1] int32     w_gate, w_up [E,I,H] bf16     w_down [E,H,I] bf16
- *   dy_perm  [T*K,H] bf16: dL/dy for every row
- *   d_x_perm [T*K,H] bf16 out       d_w_gate, d_w_up [E,I,H] float out       d_w_down [E,H,I] float out
+ *   x_perm   [T*K,H] dtype    expert_offsets [E+1] int32     w_gate, w_up [E,I,H] dtype    w_down [E,H,I] dtype
+ *   dy_perm  [T*K,H] dtype: dL/dy for every row
+ *   d_x_perm [T*K,H] dtype out      d_w_gate, d_w_up [E,I,H] float out       d_w_down [E,H,I] float out
  */
 moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x_perm, const int32_t *expert_offsets,
                                          const void *w_gate, const void *w_up, const void *w_down, const void *dy_perm,
@@ -54,9 +57,9 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
 
 /*
  * Backward of moe_forward: all gradients of <out, d_out> in one call.
- *   x [T,H], w_router [E,H], w_gate, w_up [E,I,H], w_down [E,H,I]: bf16; router_bias [E] float or NULL
- *   d_out [T,H] bf16
- *   d_x [T,H] bf16 out      d_w_router [E,H] float out      d_router_bias [E] float out or NULL
+ *   x [T,H], w_router [E,H], w_gate, w_up [E,I,H], w_down [E,H,I]: dtype; router_bias [E] float or NULL
+ *   d_out [T,H] dtype
+ *   d_x [T,H] dtype out     d_w_router [E,H] float out      d_router_bias [E] float out or NULL
  *   d_w_gate, d_w_up [E,I,H] float out      d_w_down [E,H,I] float out
  * Sums over the rows of an expert run in row order and sums over a token's K slots in slot order, so two calls
  * on the same inputs give the same bits.

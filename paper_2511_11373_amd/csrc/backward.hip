@@ -268,6 +268,37 @@ hipError_t zero_floats(float *p, size_t count, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Float storage: the GEMMs of this pass multiply bf16 (as the forward pass does, which rounds float inputs on load), so
+// float inputs are rounded once into bf16 copies in the workspace, and row gradients are widened on the way out.
+__global__ __launch_bounds__(256) void bw_to_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out, size_t n8) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(in + i * 8), b = *reinterpret_cast<const f32x4 *>(in + i * 8 + 4);
+        *reinterpret_cast<u32x4 *>(out + i * 8) =
+            u32x4{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+    }
+}
+__global__ __launch_bounds__(256) void bw_to_float_kernel(const bf16_t *__restrict__ in, float *__restrict__ out, size_t n8) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(in + i * 8);
+        *reinterpret_cast<f32x4 *>(out + i * 8) = f32x4{__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xFFFF0000u),
+                                                        __uint_as_float(v[1] << 16), __uint_as_float(v[1] & 0xFFFF0000u)};
+        *reinterpret_cast<f32x4 *>(out + i * 8 + 4) = f32x4{__uint_as_float(v[2] << 16), __uint_as_float(v[2] & 0xFFFF0000u),
+                                                            __uint_as_float(v[3] << 16), __uint_as_float(v[3] & 0xFFFF0000u)};
+    }
+}
+hipError_t to_bf16(const void *in, bf16_t *out, size_t count, hipStream_t st) {      // count is a multiple of 8
+    if (count == 0) return hipSuccess;
+    const size_t n8 = count / 8, blocks = (n8 + 255) / 256;
+    hipLaunchKernelGGL(bw_to_bf16_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st, (const float *)in, out, n8);
+    return hipGetLastError();
+}
+hipError_t to_float(const bf16_t *in, void *out, size_t count, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    const size_t n8 = count / 8, blocks = (n8 + 255) / 256;
+    hipLaunchKernelGGL(bw_to_float_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st, in, (float *)out, n8);
+    return hipGetLastError();
+}
+
 // Optional stage timer of the backward call: an event at every stage boundary.
 struct BwProbe {
     hipEvent_t ev[MOE_BW_NUM_STAGES + 1];
@@ -286,6 +317,9 @@ struct BwWorkspace {
     bf16_t *zeros;                      // 512 zero bytes: what the large-batch GEMMs read past an expert's last row
     int32_t *row_token;                 // [n]: the token each expert-sorted row belongs to
     float *probs;                       // [T][E], un-renormalised weights only: the full softmax, later every logit's gradient
+    // float storage only: bf16 copies of the inputs, and the row gradients before they are widened
+    bf16_t *x16, *up16, *dx16;          // [T][H] each (for moe_grouped_swiglu_backward: [n][H] each)
+    bf16_t *wr16, *wg16, *wu16, *wd16;  // [E][H], [E][I][H], [E][I][H], [E][H][I]
     size_t total;
 };
 
@@ -311,6 +345,14 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.zeros, 512);
     take(b.row_token, n * 4);
     take(b.probs, s.renormalize ? 0 : (size_t)s.T * s.E * 4);
+    const size_t f = s.dtype == MOE_F32 ? 2 : 0;      // bytes per element of the bf16 copies, none for bf16 storage
+    take(b.x16, n * s.H * f);
+    take(b.up16, n * s.H * f);
+    take(b.dx16, n * s.H * f);
+    take(b.wr16, (size_t)s.E * s.H * f);
+    take(b.wg16, (size_t)s.E * s.I * s.H * f);
+    take(b.wu16, (size_t)s.E * s.I * s.H * f);
+    take(b.wd16, (size_t)s.E * s.H * s.I * f);
     b.total = (size_t)(cur - reinterpret_cast<char *>(base));
     return b;
 }
@@ -322,7 +364,7 @@ moe_status_t check_bw_shape(const moe_shape_t *s) {
     if (s->T < 0 || s->H < 1 || s->E < 1 || s->K < 1 || s->I < 1 || s->K > s->E || s->E > kMaxExperts) return MOE_ERR_SHAPE;
     if ((s->H & 7) || (s->I & 7)) return MOE_ERR_SHAPE;
     if ((long long)s->T * s->K > 0x7FFFFFFFLL || (long long)s->T * s->E > 0x7FFFFFFFLL) return MOE_ERR_SHAPE;
-    if (s->dtype != MOE_BF16) return MOE_ERR_DTYPE;          // the backward pass is written for bf16 storage
+    if (s->dtype != MOE_BF16 && s->dtype != MOE_F32) return MOE_ERR_DTYPE;
     return MOE_OK;
 }
 
@@ -425,6 +467,19 @@ moe_status_t moe_grouped_swiglu_backward(const moe_shape_t *shape, const void *x
             return MOE_ERR_HIP;
         return MOE_OK;
     }
+    if (s.dtype == MOE_F32) {
+        const size_t nh = (size_t)s.T * s.K * s.H, wn = (size_t)s.E * s.I * s.H;
+        if (to_bf16(x_perm, b.x16, nh, hs) != hipSuccess || to_bf16(dy_perm, b.up16, nh, hs) != hipSuccess ||
+            to_bf16(w_gate, b.wg16, wn, hs) != hipSuccess || to_bf16(w_up, b.wu16, wn, hs) != hipSuccess ||
+            to_bf16(w_down, b.wd16, wn, hs) != hipSuccess)
+            return MOE_ERR_HIP;
+        moe_shape_t sb = s;
+        sb.dtype = MOE_BF16;
+        if (expert_backward(sb, b.x16, b.up16, nullptr, nullptr, nullptr, expert_offsets, b.wg16, b.wu16, b.wd16, b, b.dx16, d_w_gate,
+                            d_w_up, d_w_down, hs) != hipSuccess)
+            return MOE_ERR_HIP;
+        return to_float(b.dx16, d_x_perm, nh, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    }
     return expert_backward(s, (const bf16_t *)x_perm, (const bf16_t *)dy_perm, nullptr, nullptr, nullptr, expert_offsets,
                            (const bf16_t *)w_gate, (const bf16_t *)w_up, (const bf16_t *)w_down, b, (bf16_t *)d_x_perm,
                            d_w_gate, d_w_up, d_w_down, hs) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
@@ -474,6 +529,23 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     }
     bf16_t *dxp = (bf16_t *)w.y_perm;
     if (probe) { probe->st = hs; probe->mark(); }
+    // Float storage: the router below still sees the float values (so that it selects what the forward pass selected);
+    // everything after it works on bf16 copies, under a shape that says so.
+    const void *x_in = x, *w_router_in = w_router;
+    const moe_shape_t s_in = s;
+    moe_shape_t sb = s;
+    sb.dtype = MOE_BF16;
+    void *d_x_out = d_x;
+    if (s_in.dtype == MOE_F32) {
+        if (g_rows || u_rows) return MOE_ERR_DTYPE;      // the saving pair is bf16 only
+        const size_t th = (size_t)s.T * s.H, wn = (size_t)s.E * s.I * s.H;
+        if (to_bf16(x, b.x16, th, hs) != hipSuccess || to_bf16(d_out, b.up16, th, hs) != hipSuccess ||
+            to_bf16(w_router, b.wr16, (size_t)s.E * s.H, hs) != hipSuccess || to_bf16(w_gate, b.wg16, wn, hs) != hipSuccess ||
+            to_bf16(w_up, b.wu16, wn, hs) != hipSuccess || to_bf16(w_down, b.wd16, wn, hs) != hipSuccess)
+            return MOE_ERR_HIP;
+        x = b.x16; d_out = b.up16; w_router = b.wr16; w_gate = b.wg16; w_up = b.wu16; w_down = b.wd16;
+        d_x = b.dx16;
+    }
     // the routing: the caller's (kept from the forward pass), or recomputed
     const bool routed = topk_idx_saved && topk_w_saved;
     const int32_t *topk_idx = routed ? topk_idx_saved : w.topk_idx;
@@ -481,28 +553,28 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
     // Un-renormalised weights need the softmax over all experts: the router runs even when the routing was handed over
     // (its partial logit sums are what the probabilities are computed from).
     const bool dense = !s.renormalize;
-    if ((!routed || dense) && launch_route(s, x, w_router, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess)
+    if ((!routed || dense) && launch_route(s_in, x_in, w_router_in, router_bias, w.logit_part, w.topk_idx, w.topk_w, hs) != hipSuccess)
         return MOE_ERR_HIP;
-    if (dense && launch_router_probs(s, w.logit_part, router_bias, b.probs, hs) != hipSuccess) return MOE_ERR_HIP;
+    if (dense && launch_router_probs(s_in, w.logit_part, router_bias, b.probs, hs) != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);
-    if (launch_permute(s, topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
+    if (launch_permute(sb, topk_idx, w.expert_offsets, w.row_to_assign, w.assign_to_row, w.chunk_base, hs) != hipSuccess)
         return MOE_ERR_HIP;
     // Shapes the LDS-pipelined GEMMs take: they fetch the rows of x and d_out through a row -> token map (both then stay
     // in the caches instead of being streamed back K times over).  Otherwise: copies of x and d_out in expert-sorted row
     // order, so that the LDS-free GEMMs address their rows by plain arithmetic.
-    const bool mapped = rows_through_map(s);
+    const bool mapped = rows_through_map(sb);
     const bf16_t *x_rows = mapped ? (const bf16_t *)x : b.x_perm, *up_rows = mapped ? (const bf16_t *)d_out : b.up_perm;
     const int32_t *row_token = mapped ? b.row_token : nullptr;
     if (mapped) {
         hipLaunchKernelGGL(bw_row_token_kernel, dim3((s.T * s.K + 255) / 256), dim3(256), 0, hs, w.row_to_assign, s.K, s.T * s.K,
                            b.row_token);
         if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    } else if (launch_gather_rows(s, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
-               launch_gather_rows(s, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess) {
+    } else if (launch_gather_rows(sb, x, w.row_to_assign, b.x_perm, hs) != hipSuccess ||
+               launch_gather_rows(sb, d_out, w.row_to_assign, b.up_perm, hs) != hipSuccess) {
         return MOE_ERR_HIP;
     }
     bw_mark(probe);
-    if (expert_backward(s, x_rows, up_rows, row_token, w.row_to_assign, topk_w, w.expert_offsets, (const bf16_t *)w_gate,
+    if (expert_backward(sb, x_rows, up_rows, row_token, w.row_to_assign, topk_w, w.expert_offsets, (const bf16_t *)w_gate,
                         (const bf16_t *)w_up, (const bf16_t *)w_down, b, dxp, d_w_gate, d_w_up, d_w_down, hs, probe,
                         (const bf16_t *)g_rows, (const bf16_t *)u_rows) != hipSuccess)
         return MOE_ERR_HIP;
@@ -527,6 +599,7 @@ static moe_status_t backward_impl(const moe_shape_t *shape, const void *x, const
                            d_w_router, d_router_bias, s.H, 0, 1);
         if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
     }
+    if (s_in.dtype == MOE_F32 && to_float(b.dx16, d_x_out, (size_t)s.T * s.H, hs) != hipSuccess) return MOE_ERR_HIP;
     bw_mark(probe);
     bw_mark(probe);       // closes the empty calibration interval
     return MOE_OK;

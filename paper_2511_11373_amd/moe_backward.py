@@ -53,7 +53,7 @@ def alloc_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:
 def moe_grouped_swiglu_backward(shape: MoeShape, x_perm, expert_offsets, w_gate, w_up, w_down, dy_perm, ws) -> Dict[str, torch.Tensor]:
     n = shape.T * shape.K
     dev = x_perm.device
-    out = {"d_x_perm": torch.empty((n, shape.H), dtype=torch.bfloat16, device=dev),
+    out = {"d_x_perm": torch.empty((n, shape.H), dtype=x_perm.dtype, device=dev),
            "d_w_gate": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),
            "d_w_up": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),
            "d_w_down": torch.empty((shape.E, shape.H, shape.I), dtype=torch.float32, device=dev)}
@@ -67,7 +67,7 @@ def moe_backward(shape: MoeShape, x, w_router, router_bias: Optional[torch.Tenso
                  out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
     dev = x.device
     if out is None:
-        out = {"d_x": torch.empty((shape.T, shape.H), dtype=torch.bfloat16, device=dev),
+        out = {"d_x": torch.empty((shape.T, shape.H), dtype=x.dtype, device=dev),
                "d_w_router": torch.empty((shape.E, shape.H), dtype=torch.float32, device=dev),
                "d_router_bias": torch.empty((shape.E,), dtype=torch.float32, device=dev),
                "d_w_gate": torch.empty((shape.E, shape.I, shape.H), dtype=torch.float32, device=dev),

@@ -140,7 +140,7 @@ def test_backward_validation_on_the_host(lib):
     need = ctypes.c_size_t(0)
     assert lib.moe_backward_workspace_bytes(ctypes.byref(good), ctypes.byref(need)) == 0
     assert need.value % 256 == 0 and need.value > moe.workspace_bytes(good)
-    for shape, code in ((moe.make_shape(4, 64, 8, 2, 32, moe.MOE_F32), 3),
+    for shape, code in ((moe.make_shape(4, 64, 8, 2, 32, 7), 3),
                         (moe.make_shape(4, 60, 8, 2, 32, moe.MOE_BF16), 2), (moe.make_shape(4, 64, 8, 9, 32, moe.MOE_BF16), 2)):
         assert lib.moe_backward_workspace_bytes(ctypes.byref(shape), ctypes.byref(need)) == code
         assert lib.moe_backward(ctypes.byref(shape), *a, 1 << 40, None) == code

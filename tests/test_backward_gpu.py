@@ -27,21 +27,25 @@ def _cmp(got, ref, what):
     return check_close(host(got), ref, what, max_abs=2e-2 * scale, rel_l2=1e-2)
 
 
-@pytest.mark.parametrize("counts,H,I", [([0, 70, 0, 33, 256, 1, 300, 0], 136, 72),
-                                        ([0, 700, 0, 257, 256, 1, 0, 900, 3, 0], 128, 64)],     # the second takes the LDS-pipelined kernels
-                         ids=["small", "large"])
-def test_grouped_swiglu_backward_uneven_segments(oracle_lib, counts, H, I):
+@pytest.mark.parametrize("counts,H,I,dtype", [([0, 70, 0, 33, 256, 1, 300, 0], 136, 72, wl.BF16),
+                                              ([0, 700, 0, 257, 256, 1, 0, 900, 3, 0], 128, 64, wl.BF16),     # takes the LDS-pipelined kernels
+                                              ([3, 0, 260, 41], 128, 64, wl.F32)],
+                         ids=["small", "large", "float"])
+def test_grouped_swiglu_backward_uneven_segments(oracle_lib, counts, H, I, dtype):
     n, E = sum(counts), len(counts)
-    cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=41, sigma_w=0.1)
+    cfg = wl.small_config(n, H, E, 1, I, dtype=dtype, seed=41, sigma_w=0.1)
     d = wl.make_inputs(cfg)
     g = upload(cfg, d)
     rng = np.random.default_rng(41)
     dy_bits, dy = _bf16_normal(rng, (n, H))
+    if dtype == wl.F32:
+        dy_bits = dy
     off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
     shp = shape_of(cfg)
     ws = mb.alloc_workspace(shp)
     out = mb.moe_grouped_swiglu_backward(shp, g["x"], torch.from_numpy(off).cuda(), g["w_gate"], g["w_up"], g["w_down"],
-                                         to_dev(dy_bits, wl.BF16), ws)
+                                         to_dev(dy_bits, dtype), ws)
+    assert out["d_x_perm"].dtype == g["x"].dtype
     ref = bwd.grouped_swiglu_backward(d["x_f32"], off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], dy)
     for name in ("d_x_perm", "d_w_gate", "d_w_up", "d_w_down"):
         _cmp(out[name], ref[name], name)
@@ -65,6 +69,10 @@ CASES = [
     wl.small_config(300, 256, 16, 4, 128, dtype=wl.BF16, seed=53, sigma_w=0.05, renormalize=False),     # with a bias (odd seed)
     wl.small_config(1500, 256, 70, 4, 64, dtype=wl.BF16, seed=54, sigma_w=0.05, renormalize=False),
     wl.small_config(40, 64, 300, 5, 16, dtype=wl.BF16, seed=55, sigma_w=0.1, renormalize=False),        # more than 256 experts
+    # float storage: the router reads the floats, everything else is rounded to bf16 on the way in
+    wl.small_config(130, 264, 6, 3, 136, dtype=wl.F32, seed=56, sigma_w=0.05),
+    wl.small_config(300, 256, 16, 4, 128, dtype=wl.F32, seed=57, sigma_w=0.05),                         # with a bias, LDS-pipelined GEMMs
+    wl.small_config(90, 128, 12, 2, 64, dtype=wl.F32, seed=58, sigma_w=0.1, renormalize=False),
 ]
 
 
@@ -95,24 +103,27 @@ def _full_softmax(oracle_lib, d, bias):
     return softmax(oracle_lib.router_logits(d["x_f32"], d["w_router_f32"], bias).astype(np.float64), axis=1)
 
 
-@pytest.mark.parametrize("cfg", CASES, ids=[c.name + ("" if c.renormalize else "-norenorm") for c in CASES])
+@pytest.mark.parametrize("cfg", CASES, ids=[c.name + ("" if c.renormalize else "-norenorm") + "-" + c.dtype for c in CASES])
 def test_backward_against_oracle(oracle_lib, cfg):
     d = wl.make_inputs(cfg)
     g = upload(cfg, d)
     rng = np.random.default_rng(cfg.seed)
     bias = (rng.standard_normal(cfg.E) * 0.1).astype(np.float32) if cfg.seed % 2 else None
     do_bits, do = _bf16_normal(rng, (cfg.T, cfg.H))
+    if cfg.dtype == wl.F32:       # float storage: d_out is float too (values a bf16 holds, so that the oracle sees what the GPU multiplies)
+        do_bits = do
     shp = shape_of(cfg)
     ws = mb.alloc_workspace(shp)
     bias_dev = None if bias is None else torch.from_numpy(bias).cuda()
-    out = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    out = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, cfg.dtype), ws)
+    assert out["d_x"].dtype == g["x"].dtype
     o_idx, o_w = oracle_lib.route_topk(d["x_f32"], d["w_router_f32"], cfg.K, bias, cfg.renormalize)
     ref = bwd.backward(d["x_f32"], d["w_router_f32"], bias, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], o_idx, do, cfg.renormalize)
     for name in ("d_x", "d_w_router", "d_w_gate", "d_w_up", "d_w_down"):
         _cmp(out[name], ref[name], name)
     _cmp_bias(out["d_router_bias"], ref, o_idx, o_w, None if cfg.renormalize else _full_softmax(oracle_lib, d, bias))
     # a second call gives the same bits
-    out2 = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, wl.BF16), ws)
+    out2 = mb.moe_backward(shp, g["x"], g["w_router"], bias_dev, g["w_gate"], g["w_up"], g["w_down"], to_dev(do_bits, cfg.dtype), ws)
     for name in out:
         assert torch.equal(out[name], out2[name]), name
 
@@ -210,10 +221,10 @@ def test_saving_pair_restrictions():
 
 
 def test_backward_restrictions_and_empty_batch():
-    shp = moe.make_shape(8, 64, 4, 2, 32, moe.MOE_F32)
     with pytest.raises(moe.MoeError) as e:
-        mb.workspace_bytes(shp)
+        mb.workspace_bytes(moe.make_shape(8, 64, 4, 2, 32, 7))        # no such storage type
     assert e.value.code == 3
+    assert mb.workspace_bytes(moe.make_shape(8, 64, 4, 2, 32, moe.MOE_F32)) > mb.workspace_bytes(moe.make_shape(8, 64, 4, 2, 32, moe.MOE_BF16))
     assert mb.workspace_bytes(moe.make_shape(8, 64, 4, 2, 32, moe.MOE_BF16, renormalize=False)) > \
         mb.workspace_bytes(moe.make_shape(8, 64, 4, 2, 32, moe.MOE_BF16))      # room for the softmax over all experts
     shp = moe.make_shape(0, 64, 4, 2, 32, moe.MOE_BF16)
