@@ -25,17 +25,17 @@ DEFAULT_STEPS = {"tiny": 200, "decode64": 400, "decode512": 300, "prefill16k": 4
 HBM_BOUND = ("decode64", "decode512")
 # HBM traffic of the gate/up kernel per launch, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this
 # script (KiB per dispatch, averaged), scaled by what the same counters read for a plain 393216 KiB copy kernel in
-# the same runs (FETCH_SIZE 196667 -> x2.0, WRITE_SIZE 393216 -> x1.0).  Valid only for the kernel source whose
+# the same runs (FETCH_SIZE 196652 -> x2.0, WRITE_SIZE 393216 -> x1.0).  Valid only for the kernel source whose
 # hash is recorded; after any change to that file the bench reports null until the counters are taken again.
 TRAFFIC = {
-    "decode64": {"source": "grouped_swiglu_stream.hip", "sha256_16": "5de0e597a26c419a",
-                 "fetch_kib": 385068.4, "write_kib": 778.5, "fetch_scale": 2.0, "write_scale": 1.0},
+    "decode64": {"source": "grouped_swiglu_stream.hip", "sha256_16": "ba3da780065582d9",
+                 "fetch_kib": 385073.1, "write_kib": 790.2, "fetch_scale": 2.0, "write_scale": 1.0},
     "attn64": {"source": "attn_decode.hip", "sha256_16": "e8bc56f296527f59",
                "fetch_kib": 4023095.8, "write_kib": 9335.4, "fetch_scale": 2.0, "write_scale": 1.0},
     "logprob16k": {"source": "grpo.hip", "sha256_16": "1d6b06c37e215813",
                    "fetch_kib": 2432523.5, "write_kib": 515.8, "fetch_scale": 2.0, "write_scale": 1.0},
-    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "865ffcc8e2206be7",
-                   "fetch_kib": 1354961.6, "write_kib": 196610.0, "fetch_scale": 2.0, "write_scale": 1.0},
+    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "44301c3e7eed9f1f",
+                   "fetch_kib": 1611269.2, "write_kib": 196609.0, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 

@@ -36,7 +36,11 @@
  *     device-to-host copy happens inside any call.
  *   - Inputs are read-only.  Outputs are overwritten in full.
  *   - Arguments are validated on the host before any HIP call is made; a
- *     failed validation enqueues nothing.  T == 0 is MOE_OK and enqueues nothing.
+ *     failed validation enqueues nothing.  T == 0 is MOE_OK and enqueues nothing:
+ *     every output that has elements is then left as it was, which only concerns
+ *     moe_permute's expert_offsets (E+1 values whatever T is; all zero in meaning).
+ *   - The one thing any entry point creates is the set of HIP events of the two
+ *     stage-timing calls, destroyed before they return.
  *   - Every data pointer must be 16-byte aligned.  H and I must be multiples
  *     of 8.  Non-finite inputs give undefined results.
  *   - dtype names the storage type of x, of every weight, of x_perm/y_perm and

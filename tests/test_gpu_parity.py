@@ -152,9 +152,10 @@ def test_near_ties_go_through_the_exact_recheck(lib, oracle_lib):
 
 def test_grouped_gemm_uneven_experts(lib, oracle_lib):
     """The large-batch GEMM on hand-made expert segments: experts without rows at the start, in the middle and at
-    the end, segments of 1, 3, 256 and 257 rows, and one expert that holds most of the rows and therefore spans
-    several of the per-XCD shares of the row-tile list."""
-    counts = [0, 700, 0, 257, 256, 1, 0, 2500, 3, 0, 512, 0]
+    the end, segments of 1, 3, 256 and 257 rows, segments around the row counts at which a tile changes from one main loop
+    to another (64, 65, 128, 129, 255), and one expert that holds most of the rows and therefore spans several of the
+    per-XCD shares of the row-tile list."""
+    counts = [0, 700, 64, 257, 256, 1, 65, 2500, 3, 128, 512, 129, 255, 0]      # 64 / 65 / 128 / 129: around the short-tile loops' limits
     n, H, I, E = sum(counts), 256, 128, len(counts)
     cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=31, sigma_w=0.05)
     d = wl.make_inputs(cfg)
