@@ -480,14 +480,14 @@ def main():
     if cfg.name == "decode64" and not args.no_prefill_record:
         pcfg = wl.CONFIGS["prefill16k"]
         px = dev(wl.make_inputs(pcfg, want_f32=False, only=("x",))["x"])
-        p_steps = 20
-        p_ms, p_stage, p_load, p_out, _ = measure(pcfg, px, None, p_steps, 4)
+        p_steps, p_warm = 40, 10
+        p_ms, p_stage, p_load, p_out, _ = measure(pcfg, px, None, p_steps, p_warm)
         p_flops = 2.0 * pcfg.T * pcfg.K * 3 * pcfg.I * pcfg.H
         p_empty = float(p_stage[moe.STAGE_NAMES.index("empty_interval")])
         p_gu = float(p_stage[moe.STAGE_NAMES.index("gate_up_gemm")]) - p_empty
         p_dn = float(p_stage[moe.STAGE_NAMES.index("down_gemm")]) - p_empty
         layer["prefill16k"] = {
-            "workload": "prefill16k", "tokens": pcfg.T, "steps": p_steps, "warmup": 4, "ms_per_step": round(p_ms, 5),
+            "workload": "prefill16k", "tokens": pcfg.T, "steps": p_steps, "warmup": p_warm, "ms_per_step": round(p_ms, 5),
             "tokens_per_s": round(pcfg.T / (p_ms * 1e-3), 1), "algorithmic_GFLOP": round(p_flops / 1e9, 2),
             "mfma_frac_whole_step": round(p_flops / (p_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "gate_up_gemm": {"avg_launch_ms": round(p_gu, 5),
