@@ -47,15 +47,17 @@ static bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 
 static size_t elt_size(const moe_shape_t &s) { return s.dtype == MOE_BF16 ? 2 : 4; }
 
+// Addresses are carved as integers: the same code sizes a workspace from a null base, and pointer arithmetic on a null
+// pointer is undefined.
 template <typename P>
-static void take(char *&cur, P *&field, size_t bytes) {
+static void take(uintptr_t &cur, P *&field, size_t bytes) {
     field = reinterpret_cast<P *>(cur);
     cur += align256(bytes);
 }
 
 Workspace carve_workspace(const moe_shape_t &s, void *base) {
     Workspace w;
-    char *cur = reinterpret_cast<char *>(base);
+    uintptr_t cur = reinterpret_cast<uintptr_t>(base);
     const size_t n = (size_t)s.T * s.K;
     const size_t nchunks = (n + kPermChunk - 1) / kPermChunk;
     const size_t max_tiles = n / kMinTokenTile + (size_t)s.E;
@@ -72,7 +74,7 @@ Workspace carve_workspace(const moe_shape_t &s, void *base) {
     void *y = nullptr;
     take(cur, y, elt_size(s) * n * s.H);
     w.y_perm = y;
-    w.total = (size_t)(cur - reinterpret_cast<char *>(base));
+    w.total = (size_t)(cur - reinterpret_cast<uintptr_t>(base));
     return w;
 }
 
@@ -114,7 +116,10 @@ using namespace moe;
 extern "C" {
 
 const char *moe_status_string(moe_status_t status) {
-    switch (status) {
+    // a C caller may pass any int: read the bits, not the enumeration (whose other values C++ leaves undefined)
+    int code;
+    __builtin_memcpy(&code, &status, sizeof code);
+    switch (code) {
         case MOE_OK: return "ok";
         case MOE_ERR_NULL: return "a required pointer is NULL";
         case MOE_ERR_SHAPE: return "unsupported shape";

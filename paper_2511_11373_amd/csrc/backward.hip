@@ -326,7 +326,7 @@ struct BwWorkspace {
 BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     BwWorkspace b;
     b.fwd = carve_workspace(s, base);
-    char *cur = reinterpret_cast<char *>(base) + b.fwd.total;
+    uintptr_t cur = reinterpret_cast<uintptr_t>(base) + b.fwd.total;      // integers: the base is null when only sizing
     const size_t n = (size_t)s.T * s.K;
     auto take = [&](auto *&field, size_t bytes) {
         field = reinterpret_cast<std::remove_reference_t<decltype(field)>>(cur);
@@ -353,7 +353,7 @@ BwWorkspace carve_bw(const moe_shape_t &s, void *base) {
     take(b.wg16, (size_t)s.E * s.I * s.H * f);
     take(b.wu16, (size_t)s.E * s.I * s.H * f);
     take(b.wd16, (size_t)s.E * s.H * s.I * f);
-    b.total = (size_t)(cur - reinterpret_cast<char *>(base));
+    b.total = (size_t)(cur - reinterpret_cast<uintptr_t>(base));
     return b;
 }
 
