@@ -184,3 +184,36 @@ def test_twenty_backward_runs_give_the_same_bits(lib, family):
             ref = out
         for name in out:
             assert torch.equal(out[name], ref[name]), (family, run, name)
+
+
+def test_forward_replays_from_a_hip_graph(lib, oracle_lib):
+    """A serving loop captures the decode step once and replays it: every entry point only enqueues kernels on the caller's
+    stream (no allocation, no synchronisation, no memset, no event), so the whole block records into a HIP graph.  Replays
+    with the program's own eager work and synchronisations in between, on inputs changed in place, must give what an eager
+    call gives; both the workspace form and the form on the library's static scratch."""
+    cfg = wl.small_config(64, 2048, 16, 2, 768, dtype=wl.BF16, seed=71)
+    d = wl.make_inputs(cfg, want_f32=False)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    x = g["x"].clone()
+    outs = {"workspace": torch.empty_like(x), "static scratch": torch.empty_like(x)}
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    moe.moe_forward_noalloc(shp, x, g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], outs["static scratch"])   # symbol lookup happens here, not under capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        moe.moe_forward(shp, x, g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], ws, out=outs["workspace"], topk_idx_out=idx)
+        moe.moe_forward_noalloc(shp, x, g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], outs["static scratch"])
+    rng = np.random.default_rng(5)
+    for replay in range(4):
+        new_x = to_dev(wl.f32_to_bf16_bits(rng.standard_normal((cfg.T, cfg.H)).astype(np.float32)), wl.BF16)
+        x.copy_(new_x)
+        for o in outs.values():
+            o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = moe.moe_forward(shp, new_x, g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], moe.alloc_workspace(shp))
+        torch.cuda.synchronize()
+        for name, o in outs.items():
+            assert torch.equal(o, eager), (name, replay)
