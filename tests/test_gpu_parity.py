@@ -268,3 +268,29 @@ def test_full_size_expert_rows_every_element(lib, oracle_lib):
     check_close(got, o_y, "y_perm[skew4k], all rows")
     row_rel = np.linalg.norm(got - o_y, axis=1) / np.maximum(np.linalg.norm(o_y, axis=1), 1e-30)
     assert row_rel.max() <= 2e-2, (int(row_rel.argmax()), float(row_rel.max()))
+
+
+def test_rows_past_32_bit_element_indices(lib, oracle_lib):
+    """131072 tokens at the layer shape: 1 048 576 expert-sorted rows, 2.1e9 elements of y_perm - past what a 32-bit element
+    index holds - and 512 row tiles per expert.  Routing and permutation of every token exactly; the output on sampled tokens,
+    among them the tokens whose rows are the last ones of the sorted order."""
+    cfg = wl.MoEConfig("prefill128k", 131072, 2048, 128, 8, 768, wl.BF16, seed=3)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    idx = torch.empty((cfg.T, cfg.K), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg.T, cfg.K), dtype=torch.float32, device="cuda")
+    out = moe.moe_forward(shp, g["x"], g["w_router"], None, g["w_gate"], g["w_up"], g["w_down"], ws, topk_idx_out=idx, topk_w_out=w)
+    o_idx, o_w, o_off, o_r2a, o_a2r = _oracle_all(oracle_lib, cfg, d)
+    assert np.array_equal(host(idx), o_idx)
+    check_weights(host(w), o_w)
+    off, r2a, a2r, _ = moe.moe_permute(shp, idx, g["x"], ws, want_x_perm=False)
+    assert np.array_equal(host(off), o_off) and np.array_equal(host(r2a), o_r2a) and np.array_equal(host(a2r), o_a2r)
+    rng = np.random.default_rng(9)
+    tok = np.concatenate([[0, cfg.T - 1], rng.integers(0, cfg.T, 90), o_r2a[-32:] // cfg.K, o_r2a[:4] // cfg.K])
+    tok = np.unique(tok).astype(np.int32)
+    ref = oracle_lib.forward_tokens(d["x_f32"], o_idx, o_w, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"], tok)
+    got = host(out[torch.from_numpy(tok).long().cuda()])
+    check_close(got, ref, "forward at 131072 tokens, sampled tokens")
+    assert bool(torch.isfinite(out.float()).all().item())
