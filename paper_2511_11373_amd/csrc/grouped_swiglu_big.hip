@@ -1,5 +1,6 @@
 // Large-batch grouped GEMM for bf16 storage: 256 weight rows x 256 token rows per block, direct
-// global->LDS loads (no register staging), two LDS stages, 32x32x16 bf16 MFMA.
+// global->LDS loads (no register staging), 64-wide k stages in LDS rings (three for the weights, two for the token rows),
+// 32x32x16 bf16 MFMA.
 //
 // Block = 4 waves in a 2 (weight) x 2 (token) grid; a wave owns 4 weight tiles x 4 token tiles of
 // 32x32, i.e. 16 accumulators (256 VGPRs).  For the gate/up pass the 256 weight rows are 128 rows of
@@ -185,8 +186,9 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     auto read_live = [&](int q) { return q == 5 ? nb > 1 : q == 6 ? nb > 2 : q == 7 ? nb > 3 : nb > 0; };
     // One 16-wide k step: 16 MFMAs out of operand set ks&1.  A wave is alone on its SIMD, so an instruction
     // that is not an MFMA only comes for free in the shadow of the MFMA issued just before it (the matrix
-    // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step and, in a stage's last
-    // k step, the 16 global->LDS loads are therefore dealt out one per MFMA.
+    // pipe is busy for 8 passes per MFMA): the 8 operand reads of the following k step are therefore dealt out one per
+    // MFMA, and the global->LDS loads at most one per two MFMAs - issued back to back they queue up in front of the
+    // texture unit and hold up the MFMAs behind them (all 16 of a stage in one k step: 7 % slower).
     auto kstep = [&](auto mode_c, int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wn,
                      unsigned char *Xn, int k_w, int k_x) {
         constexpr bool FULL = decltype(mode_c)::full;
@@ -204,11 +206,14 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
                     acc[a2][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[set][a2], bop[set][b], acc[a2][b], 0, 0, 0);
             }
             if (m < 8 && (FULL || read_live(m))) read_one(wa, xa, set ^ 1, m);
-            if (ks == 3) {
-                // long tiles: the 8 token loads first, then the 8 weight loads (the wait in front of the next barrier lets
-                // exactly the weight loads stay under way); short tiles: weight and token loads alternate
-                const int j = NX > 0 ? m : (m < 8 ? 2 * m + 1 : 2 * (m - 8));
-                if (NX == 0 || !(j & 1) || (j >> 1) < NX) issue(Wn, Xn, (j & 1) ? k_x : k_w, j);
+            if (NX > 0) {
+                // short tiles: all loads in the last k step, weight and token loads alternating
+                if (ks == 3 && (!(m & 1) || (m >> 1) < NX)) issue(Wn, Xn, (m & 1) ? k_x : k_w, m);
+            } else {
+                // long tiles: the 8 token loads in the last k step (one per two MFMAs), the 8 weight loads in the first two
+                // k steps (one per four MFMAs); the wait in front of the barrier lets exactly the weight loads stay under way
+                if (ks == 3 && (m & 1)) issue(Wn, Xn, k_x, 2 * (m >> 1) + 1);
+                if (ks < 2 && (m & 3) == 3) issue(Wn, Xn, k_w, 2 * (ks * 4 + (m >> 2)));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -220,10 +225,12 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     // and its own loads of the next stage have landed, so behind the barrier the current buffers are free in every wave
     // and the next ones complete.  The last k step therefore reads the first operands of the next stage and issues
     // loads into the buffers just freed.
-    // Long tiles keep the weights in a ring of three stages and the token rows in a ring of two: the token rows of the
-    // stage after the next are issued there (three k steps to arrive: they come from L2 or the last-level cache, each
-    // row being read by 48 blocks) and the WEIGHTS of the stage after that, which therefore have a whole stage more,
-    // seven k steps, to arrive - a weight tile is read by four blocks only and often comes from HBM.  The last stages
+    // Long tiles keep the weights in a ring of three stages and the token rows in a ring of two.  The token rows of the
+    // stage after the next are issued in that last k step, into the buffer just freed (three k steps to arrive: they
+    // come from L2 or the last-level cache, each row being read by 48 blocks).  The WEIGHTS of the stage after the next
+    // are issued earlier, during the first two k steps of the current stage, into the third weight buffer, which the
+    // stage before this one left: they have six to seven k steps to arrive - a weight tile is read by four blocks only
+    // and often comes from HBM - and the loads of a stage are spread over three k steps instead of one.  The last stages
     // reload the final k tile instead of branching around the loads.  Every wave issues all 16 loads of a stage, live
     // token rows or not (rows past the tile's end are other rows of the batch), so the waits can count.
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
@@ -240,8 +247,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
         all_loads(w_cur, x_cur, 0, 1);
         all_loads(w_nxt, x_nxt, min(BK, k_last), 0);
         all_loads(w_nxt, x_nxt, min(BK, k_last), 1);
-        all_loads(w_aft, x_cur, min(2 * BK, k_last), 0);
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // stage 0 has landed
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");      // stage 0 has landed
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int q = 0; q < 8; ++q)
@@ -249,11 +255,13 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
 #pragma unroll 1
         for (int kt = 0; kt < nk; ++kt) {
             const unsigned wcur = lds_addr(w_cur), xcur = lds_addr(x_cur), wnxt = lds_addr(w_nxt), xnxt = lds_addr(x_nxt);
-            const int k_w = min((kt + 3) * BK, k_last), k_x = min((kt + 2) * BK, k_last);
+            // weights of stage kt + 2: during k steps 0 and 1, into the buffer that stage kt - 1 left (w_aft); token rows of
+            // stage kt + 2: during k step 3, into this stage's buffer
+            const int k_w = min((kt + 2) * BK, k_last), k_x = min((kt + 2) * BK, k_last);
             wait_lds_reads<0>(aop[0], bop[0]);
-            kstep(mode_c, 0, wcur, xcur, 1, w_cur, x_cur, k_w, k_x);
+            kstep(mode_c, 0, wcur, xcur, 1, w_aft, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[1], bop[1]);
-            kstep(mode_c, 1, wcur, xcur, 2, w_cur, x_cur, k_w, k_x);
+            kstep(mode_c, 1, wcur, xcur, 2, w_aft, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[0], bop[0]);
             kstep(mode_c, 2, wcur, xcur, 3, w_cur, x_cur, k_w, k_x);
             wait_lds_reads<0>(aop[1], bop[1]);
