@@ -1,8 +1,9 @@
 // Large-batch grouped GEMMs of the backward pass: the forward pass's 256 x 256 x 64 LDS pipeline with operands that
 // are stored ACROSS the reduction axis read out of LDS by the transposing LDS load.
 //
-// out[x][f] = sum_k X[x][k] * W[f][k], 32x32x16 bf16 MFMAs, 4 waves in a 2 x 2 grid, 16 accumulators per wave, two LDS
-// stages of 32 KB per operand, every operand brought in by global_load_lds two stages ahead, one block barrier per
+// out[x][f] = sum_k X[x][k] * W[f][k], 32x32x16 bf16 MFMAs, 4 waves in a 2 x 2 grid, 16 accumulators per wave, LDS
+// stages of 32 KB per operand (a ring of three for the operand whose loads go out early, of two for the other), every
+// operand brought in by global_load_lds two stages ahead with the loads spread over three k steps, one block barrier per
 // stage in front of its last k step - all as in grouped_swiglu_big.hip.  What differs is how an operand lies in LDS:
 //   * stored along k (the token-row operand of the data gradients): 256 rows x 128 bytes, 16-byte piece j of row r at
 //     position j ^ ((r >> 1) & 7), read with ds_read_b128, as there;
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     __shared__ __attribute__((aligned(1024))) unsigned char XsA[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char WsB[OPB];
     __shared__ __attribute__((aligned(1024))) unsigned char XsB[OPB];
+    __shared__ __attribute__((aligned(1024))) unsigned char ThirdS[OPB];      // third stage of the operand that is loaded early
 
     // ---- which tile: blocks go round-robin to the 8 XCDs ------------------------------------------------------
     const int slot = blockIdx.x >> 3;
@@ -226,9 +228,13 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     constexpr int NREAD = WGRAD ? 16 : 12;
     const unsigned wsA = lds_addr(WsA), xsA = lds_addr(XsA), wsB = lds_addr(WsB), xsB = lds_addr(XsB);
 
-    // One k step: 16 MFMAs out of operand set ks & 1, each followed by one read of the next k step's operands and, in
-    // the last k step of a stage (behind the barrier), by one load of stage `s_load` into the buffer just freed.
-    auto kstep = [&](int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *Wl, unsigned char *Xl, int s_load) {
+    // One k step: 16 MFMAs out of operand set ks & 1, each followed by one read of the next k step's operands; the loads
+    // of stage `s_load` are dealt out at most one per two MFMAs (back to back they hold up the MFMAs behind them).
+    // The operand that is NOT addressed through a row map is the early one: its loads of stage s_load go out during the
+    // first two k steps (one per four MFMAs) into the third buffer of its ring; the other operand's loads follow in the
+    // last k step (one per two MFMAs), into the buffer the barrier has just freed, with the row numbers fetched in k step 0.
+    constexpr bool EARLY_W = MAPPED != 2;
+    auto kstep = [&](int ks, unsigned wrd, unsigned xrd, int ks_rd, unsigned char *early_buf, unsigned char *late_buf, int s_load) {
         const int set = ks & 1;
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
@@ -236,7 +242,8 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aop[set][a]),
                                                                 __builtin_bit_cast(bf16x8, bop[set][b]), acc[a][b], 0, 0, 0);
             if (m < NREAD) read_one(wrd, xrd, ks_rd, set ^ 1, m);
-            if (ks == 3) issue(s_load, Wl, Xl, m, tk);
+            if (ks < 2 && (m & 3) == 3) issue(s_load, early_buf, early_buf, 2 * (ks * 4 + (m >> 2)) + (EARLY_W ? 0 : 1), tk);
+            if (ks == 3 && (m & 1)) issue(s_load, late_buf, late_buf, 2 * (m >> 1) + (EARLY_W ? 1 : 0), tk);
             if (MAPPED && ks == 0 && m < 8) load_tokens(s_load, tk, m);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -258,23 +265,31 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int q = 0; q < NREAD; ++q) read_one(wsA, xsA, 0, 0, q);
+        // rings: three buffers for the early operand, two for the late one
+        unsigned char *e_cur = EARLY_W ? WsA : XsA, *e_nxt = EARLY_W ? WsB : XsB, *e_aft = ThirdS;
+        unsigned char *l_cur = EARLY_W ? XsA : WsA, *l_nxt = EARLY_W ? XsB : WsB;
 #pragma unroll 1
         for (int kt = 0; kt < nst; ++kt) {
-            const bool odd = kt & 1;
-            const unsigned wcur = odd ? wsB : wsA, xcur = odd ? xsB : xsA;
-            const unsigned wnxt = odd ? wsA : wsB, xnxt = odd ? xsA : xsB;
-            unsigned char *Wl = odd ? WsB : WsA, *Xl = odd ? XsB : XsA;      // loads of stage kt + 2 land in the current buffers
+            const unsigned wcur = lds_addr(EARLY_W ? e_cur : l_cur), xcur = lds_addr(EARLY_W ? l_cur : e_cur);
+            const unsigned wnxt = lds_addr(EARLY_W ? e_nxt : l_nxt), xnxt = lds_addr(EARLY_W ? l_nxt : e_nxt);
             const int s_load = min(kt + 2, nst - 1);                        // past the end: the last stage again, never read
             wait_lds(aop[0], bop[0]);
-            kstep(0, wcur, xcur, 1, Wl, Xl, s_load);
+            kstep(0, wcur, xcur, 1, e_aft, l_cur, s_load);
             wait_lds(aop[1], bop[1]);
-            kstep(1, wcur, xcur, 2, Wl, Xl, s_load);
+            kstep(1, wcur, xcur, 2, e_aft, l_cur, s_load);
             wait_lds(aop[0], bop[0]);
-            kstep(2, wcur, xcur, 3, Wl, Xl, s_load);
+            kstep(2, wcur, xcur, 3, e_aft, l_cur, s_load);
             wait_lds(aop[1], bop[1]);
-            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), as the builtin: the compiler then knows that the row numbers have arrived too
+            // stage kt + 1 has landed; what may still be under way is what this stage issued: the early operand's 8 loads
+            // and, with a row map, the 8 row numbers (for those the compiler adds a wait of its own in front of their first
+            // use in the last k step, which also waits for the early loads: with a row map the ring only spreads the loads)
+            if (MAPPED) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             __builtin_amdgcn_s_barrier();
-            kstep(3, wnxt, xnxt, 0, Wl, Xl, s_load);
+            kstep(3, wnxt, xnxt, 0, e_aft, l_cur, s_load);
+            unsigned char *t = e_cur;
+            e_cur = e_nxt; e_nxt = e_aft; e_aft = t;
+            t = l_cur; l_cur = l_nxt; l_nxt = t;
         }
         wait_lds(aop[0], bop[0]);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
