@@ -412,12 +412,18 @@ __global__ __launch_bounds__(1024) void build_xcd_tile_list_kernel(const int32_t
     }
     __syncthreads();
     const int n_long = lfirst[E], n_short = sfirst[E];
-    // XCD x takes tiles [x*q + min(x, r), ...) of a kind, q = N / 8, r = N % 8: shares differ by at most one tile
+    // XCD x takes a contiguous share of each kind, q = N / 8 tiles or one more.  The r = N % 8 larger shares of the long
+    // tiles go to XCDs 0 .. rl - 1, those of the short tiles to the XCDs that follow (rl, rl + 1, ... round the ring), so
+    // that the totals differ by one tile at most: with a handful of blocks per CU, one tile more on an XCD is one more
+    // round of blocks there while the others idle (measured at 1536 tokens with a single long tile: the XCD that got
+    // both extra tiles ended at 219 us, the others at 175).
     const int ql = n_long >> 3, rl = n_long & 7, qs = n_short >> 3, rs = n_short & 7;
     for (int idx = threadIdx.x; idx < 8 * tiles_per_xcd; idx += 1024) {
         const int x = idx / tiles_per_xcd, i = idx - x * tiles_per_xcd;
-        const int l0 = x * ql + min(x, rl), s0 = x * qs + min(x, rs);
-        const int nl = ql + (x < rl), ns = qs + (x < rs), tot = nl + ns;      // <= tiles_per_xcd by the launcher's bound
+        int s_extra_before = 0;                                      // XCDs y < x with a larger share of the short tiles
+        for (int y = 0; y < x; ++y) s_extra_before += ((y - rl) & 7) < rs;
+        const int l0 = x * ql + min(x, rl), s0 = x * qs + s_extra_before;
+        const int nl = ql + (x < rl), ns = qs + (((x - rl) & 7) < rs), tot = nl + ns;      // <= tiles_per_xcd by the launcher's bound
         i32x4 ea = {-1, 0, 0, 0}, eb = {1, 0, 0, 0};
         if (i < tot) {
             // position i of the XCD's list holds a short tile when the running share of short tiles steps up there
