@@ -168,6 +168,30 @@ def test_grouped_gemm_uneven_experts(lib, oracle_lib):
     check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
 
 
+@pytest.mark.parametrize("n_long,n_short", [(7, 7), (8, 1), (9, 0), (1, 15), (5, 6), (0, 9), (16, 16), (3, 5)])
+def test_grouped_gemm_tile_shares_over_the_xcds(lib, oracle_lib, n_long, n_short):
+    """The large-batch GEMM's row tiles are dealt out to 8 lists (one per XCD), long tiles (more than 128 rows) and short
+    ones separately, the larger shares of the short ones starting where those of the long ones end.  Numbers of long and
+    short tiles around the multiples of 8, including none of a kind and a wrap of the short tiles' larger shares past the
+    last list: every row of every expert against the oracle (a tile dealt out twice or not at all would show as wrong rows)."""
+    rng = np.random.default_rng(1000 * n_long + n_short)
+    counts = [int(c) for c in rng.integers(129, 257, n_long)] + [int(c) for c in rng.integers(1, 129, n_short)]
+    rng.shuffle(counts)
+    n, H, I, E = sum(counts), 256, 128, len(counts)
+    if n < 60 * E:                                      # keep the batch on the large-batch kernel: pad with one big expert
+        counts.append(60 * (E + 1) - n + 256)
+        n, E = sum(counts), len(counts)
+    cfg = wl.small_config(n, H, E, 1, I, dtype=wl.BF16, seed=33, sigma_w=0.05)
+    d = wl.make_inputs(cfg)
+    g = upload(cfg, d)
+    shp = shape_of(cfg)
+    ws = moe.alloc_workspace(shp)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    y = moe.moe_grouped_swiglu(shp, g["x"], torch.from_numpy(off).cuda(), g["w_gate"], g["w_up"], g["w_down"], ws)
+    o_y = oracle_lib.grouped_swiglu(d["x_f32"], off, d["w_gate_f32"], d["w_up_f32"], d["w_down_f32"])
+    check_close(host(y), o_y, "y_perm", max_abs=2e-2 * max(1.0, np.abs(o_y).max()))
+
+
 def test_streaming_gemm_uneven_experts(lib, oracle_lib):
     """The decode-sized (weight-streaming) kernels on hand-made expert segments at the shape they are built for: experts
     without rows, with one row, with exactly 16, and with 17 and 33 rows (two and three passes of 16 tokens)."""
