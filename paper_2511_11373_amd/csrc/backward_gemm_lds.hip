@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256, 1) void bw_lds_kernel(const bf16_t *__restrict
     if (!WGRAD) {
         int xr[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, n_rows - 1);
+        for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, min(row_end, n_rows) - 1);      // rows past the expert's end: its last row again (one line for all of them)
         if (x_token) {                                                 // the eight row numbers in one round trip
             int token[8];
 #pragma unroll

@@ -123,13 +123,13 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     const int lrow = wave * 8 + (lane >> 3);                      // LDS row of pair 0
     const int piece = (lane & 7) ^ ((lrow >> 1) & 7);
     const bf16_t *src[16];
-    // token rows: gathered.  Rows past the expert's end belong to the next expert (or are clamped to the
-    // last row there is): they are multiplied like the others and never stored, and not having to know
-    // the expert's end here lets the gather start one memory round trip earlier.  The eight row numbers are
-    // fetched together, under one test of the map pointer: one round trip, not eight in a row.
+    // token rows: gathered.  Rows past the expert's end are replaced by its last row: they are multiplied like the
+    // others and never stored, and all lanes that stand for such a row fetch the same line, so a ragged tile takes in
+    // little more than the rows it has (the expert's end comes with the tile's list entry, at no extra round trip).
+    // The eight row numbers are fetched together, under one test of the map pointer: one round trip, not eight in a row.
     int xr[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, n_rows - 1);
+    for (int i = 0; i < 8; ++i) xr[i] = min(row0 + i * 32 + lrow, min(row_end, n_rows) - 1);
     if (row_map) {
         int assignment[8];
 #pragma unroll
