@@ -34,7 +34,7 @@ TRAFFIC = {
                "fetch_kib": 4023095.8, "write_kib": 9335.4, "fetch_scale": 2.0, "write_scale": 1.0},
     "logprob16k": {"source": "grpo.hip", "sha256_16": "1d6b06c37e215813",
                    "fetch_kib": 2432523.5, "write_kib": 515.8, "fetch_scale": 2.0, "write_scale": 1.0},
-    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "b10684dd88ec33a6",
+    "prefill16k": {"source": "grouped_swiglu_big.hip", "sha256_16": "c7946880602b4339",
                    "fetch_kib": 1360715.3, "write_kib": 196609.2, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 

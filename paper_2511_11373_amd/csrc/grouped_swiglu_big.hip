@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     // stage before this one left: they have six to seven k steps to arrive - a weight tile is read by four blocks only
     // and often comes from HBM - and the loads of a stage are spread over three k steps instead of one.  The last stages
     // reload the final k tile instead of branching around the loads.  Every wave issues all 16 loads of a stage, live
-    // token rows or not (rows past the tile's end are other rows of the batch), so the waits can count.
+    // token rows or not (rows past the tile's end are the expert's last row again), so the waits can count.
     const int nk = KD / BK;      // KD is a multiple of BK (checked by the launcher)
     const int k_last = KD - BK;
     const unsigned wsA = lds_addr(lds);
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256, 1) void grouped_gemm_big_kernel(
     // Short tiles: a ring of three stages (weights at the start of a stage, token rows behind them).  The loads of stage
     // kt + 3 are issued during the last k step of stage kt into the buffer that stage just left, so two stages' loads
     // are in flight while a stage is multiplied.  Every wave issues exactly 8 + NX loads per stage (token rows past the
-    // tile's end are other rows of the batch: loaded, multiplied into accumulators that are never stored), which is
+    // tile's end are the expert's last row again: loaded, multiplied into accumulators that are never stored), which is
     // what lets the wait in front of the barrier name the number of loads that may still be under way.
     auto run_short = [&](auto mode_c) {
         constexpr int NL = 8 + decltype(mode_c)::nx;
