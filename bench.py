@@ -30,6 +30,10 @@ HBM_BOUND = ("decode64", "decode512")
 TRAFFIC = {
     "decode64": {"source": "grouped_swiglu_stream.hip", "sha256_16": "ba3da780065582d9",
                  "fetch_kib": 385073.1, "write_kib": 790.2, "fetch_scale": 2.0, "write_scale": 1.0},
+    "decode512": {"source": "grouped_swiglu.hip", "sha256_16": "530109aef8ce97ee",
+                  "fetch_kib": 398853.9, "write_kib": 6172.7, "fetch_scale": 2.0, "write_scale": 1.0},
+    "skew4k": {"source": "grouped_swiglu_big.hip", "sha256_16": "c7946880602b4339",
+               "fetch_kib": 636461.6, "write_kib": 49153.5, "fetch_scale": 2.0, "write_scale": 1.0},
     "attn64": {"source": "attn_decode.hip", "sha256_16": "e8bc56f296527f59",
                "fetch_kib": 4023095.8, "write_kib": 9335.4, "fetch_scale": 2.0, "write_scale": 1.0},
     "logprob16k": {"source": "grpo.hip", "sha256_16": "1d6b06c37e215813",
