@@ -188,50 +188,53 @@ __global__ __launch_bounds__(256) void topk_kernel(const double *__restrict__ pa
     write_weights(sel, K, renorm, denom_all, topk_w + (size_t)t * K, lane);
 }
 
-// Same result for E <= 64*R <= 256 without a serial chain: every lane counts, for each of its
-// logits, how many (logit, id) pairs of the token precede it; that count is its slot.
+// Same result for E <= 64*R <= 256 without a serial chain: a logit's slot is the number of (logit, id) pairs of the
+// token that precede it.  One block of four waves per token.  Every wave holds all the token's logits (lane l: experts
+// l, l + 64, ...), packed with the expert id into 64-bit keys that are all different (ordered logit bits high, ~id
+// low: a larger key is a larger logit or the same logit with a lower id); each wave counts, for each of its lanes' keys,
+// the larger ones among a quarter of the token's keys (read from LDS, the same address in every lane), the four
+// counts meet in LDS, and the first wave writes the selection and its weights.
+typedef __attribute__((ext_vector_type(2))) unsigned long long u64x2;
 template <int R>
 __global__ __launch_bounds__(256) void topk_rank_kernel(const double *__restrict__ part, int ksplit,
                                                         const float *__restrict__ bias, int32_t *__restrict__ topk_idx,
                                                         float *__restrict__ topk_w, int T, int E, int K, int renorm) {
-    __shared__ __attribute__((aligned(16))) unsigned int keys_all[4][R * 64];
-    __shared__ float sel_all[4][R * 64];
+    constexpr int EP = R * 64, QK = EP / 4;
+    __shared__ __attribute__((aligned(16))) unsigned long long keys[EP];
+    __shared__ int part_rank[4][EP];
+    __shared__ float sel[EP];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int t = blockIdx.x * 4 + wave;
-    if (t >= T) return;
-    unsigned int *keys = keys_all[wave];
-    float *sel = sel_all[wave];
+    const int t = blockIdx.x;                                  // the grid has one block per token
     float logit[R];
-    unsigned int key[R];
+    unsigned long long key[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
         logit[r] = e < E ? final_logit(part, ksplit, (size_t)T * E, (size_t)t * E + e, bias, e) : 0.f;
-        key[r] = e < E ? float_order_bits(logit[r]) : 0u;     // 0 sorts below every finite float
-        keys[e] = key[r];
+        // 0 sorts below every real expert's key
+        key[r] = e < E ? ((unsigned long long)float_order_bits(logit[r]) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned int)e) : 0ull;
+        if (wave == 0) keys[e] = key[r];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();
     int rank[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) rank[r] = 0;
-    for (int e4 = 0; e4 < R * 64; e4 += 4) {
-        const u32x4 k4 = *reinterpret_cast<const u32x4 *>(&keys[e4]);
+    for (int j = 0; j < QK; j += 2) {
+        const u64x2 k2 = *reinterpret_cast<const u64x2 *>(&keys[wave * QK + j]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int e = lane + 64 * r;
-                rank[r] += (k4[j] > key[r]) || (k4[j] == key[r] && (e4 + j) < e);
-            }
+        for (int r = 0; r < R; ++r) rank[r] += (int)(k2[0] > key[r]) + (int)(k2[1] > key[r]);
     }
+#pragma unroll
+    for (int r = 0; r < R; ++r) part_rank[wave][lane + 64 * r] = rank[r];
+    __syncthreads();
+    if (wave != 0) return;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
-        if (e < E && rank[r] < K) {
-            topk_idx[(size_t)t * K + rank[r]] = e;
-            sel[rank[r]] = logit[r];
+        const int rk = part_rank[0][e] + part_rank[1][e] + part_rank[2][e] + part_rank[3][e];
+        if (e < E && rk < K) {
+            topk_idx[(size_t)t * K + rk] = e;
+            sel[rk] = logit[r];
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -635,7 +638,7 @@ hipError_t launch_route(const moe_shape_t &s, const void *x, const void *w_route
     hipLaunchKernelGGL(topk_kernel<RR>, g2, dim3(256), smem, st, logit_part, ks, bias, topk_idx, topk_w, \
                        s.T, s.E, s.K, s.renormalize)
 #define MOE_TOPK_RANK(RR)                                                                              \
-    hipLaunchKernelGGL(topk_rank_kernel<RR>, g2, dim3(256), 0, st, logit_part, ks, bias, topk_idx, topk_w, \
+    hipLaunchKernelGGL(topk_rank_kernel<RR>, dim3(s.T), dim3(256), 0, st, logit_part, ks, bias, topk_idx, topk_w, \
                        s.T, s.E, s.K, s.renormalize)
     if (r <= 1) MOE_TOPK_RANK(1);
     else if (r <= 2) MOE_TOPK_RANK(2);
